@@ -1,0 +1,292 @@
+/*
+ * tangram.h -- C ABI of the Reuse Store's Load path on one MI355X.
+ *
+ * The library implements, for one GPU, what the paper's Section 3.1 asks of a
+ * worker's Reuse Store when a model is switched in: look every tensor of the
+ * model up in the Tensor Mapping (indexed by a per-tensor fingerprint),
+ * allocate pool space for what must be placed (Section 3.2: Region List,
+ * best-fit), bring in the missing tensors from the CPU-side Model Cache,
+ * update the mapping, and hand back the GPU address of every tensor.
+ *
+ * Conventions that hold for every entry point
+ *  - Pointers marked [host] are ordinary host pointers read or written by the
+ *    CPU during the call.  Pointers marked [device] are HIP device addresses
+ *    and are only ever dereferenced by kernels or the copy engine.  Pointers
+ *    marked [pinned host] must be page-locked memory obtained from
+ *    hipHostMalloc (torch's pin_memory=True): the copy engine reads it, and
+ *    kernels read it through its device mapping.
+ *  - Ownership: the caller owns the pool slab, every host buffer and every
+ *    stream, and keeps them alive while the library uses them.  The library
+ *    owns its metadata and a small amount of device / pinned scratch
+ *    (descriptor tables, result words) that it allocates on first use and
+ *    keeps until tg_shutdown() or process exit.
+ *  - Streams are hipStream_t values passed as void* (NULL = the null stream).
+ *  - Errors: every function returns a tg_status; 0 is success, negative
+ *    values are errors, out-parameters are left untouched on error, and no
+ *    call aborts or throws across the boundary.  A failed tg_plan or
+ *    tg_assemble leaves the pool's metadata exactly as it was.
+ *  - Threading: a pool is externally synchronised (one caller at a time per
+ *    pool).  tg_fingerprint / tg_compare may be called from several threads;
+ *    they serialise on the library's scratch.
+ *  - All sizes and offsets are in bytes.  Integer arithmetic of the
+ *    fingerprint is unsigned 64-bit and wraps.
+ */
+#ifndef TANGRAM_H
+#define TANGRAM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t tg_status;
+
+#define TG_OK             0
+#define TG_ERR_INVALID   (-1)  /* null pointer, zero length, overflow, misalignment, duplicate active model */
+#define TG_ERR_NOSPACE   (-2)  /* no placement for every tensor of the model */
+#define TG_ERR_STALE     (-3)  /* the pool changed between tg_plan and tg_assemble */
+#define TG_ERR_NOTFOUND  (-4)  /* unknown model id */
+#define TG_ERR_HIP       (-5)  /* a HIP call failed (no device, launch or copy error) */
+#define TG_ERR_NOMEM     (-6)  /* host or scratch allocation failed */
+#define TG_ERR_CORRUPT   (-7)  /* TG_ASSEMBLE_VERIFY: an assembled tensor's fingerprint differs from its descriptor */
+
+/* tg_plan flags */
+#define TG_PLAN_CONFIRM   1u   /* compare bytes of every fingerprint hit before trusting it */
+/* tg_assemble flags */
+#define TG_ASSEMBLE_VERIFY 1u  /* fingerprint every assembled slot and compare with the descriptor */
+/* tg_release flags */
+#define TG_RELEASE_EVICT  1u   /* free the model's regions now instead of retaining them */
+
+/* tg_plan_op.kind */
+#define TG_OP_REUSE 0u         /* device-to-device copy from a resident tensor */
+#define TG_OP_H2D   1u         /* transfer from the model's pinned host buffer */
+
+typedef struct tg_pool tg_pool;            /* opaque; library-owned metadata of one Unified Memory Pool */
+typedef struct tg_load_plan tg_load_plan;  /* opaque; freed by tg_plan_free */
+
+/* A byte extent to fingerprint.  ptr [device] must be 16-byte aligned. */
+typedef struct {
+    const void *ptr;
+    uint64_t    nbytes;
+} tg_span;
+
+/* Two extents to compare.  a, b [device] must be 16-byte aligned. */
+typedef struct {
+    const void *a;
+    const void *b;
+    uint64_t    nbytes;
+} tg_pair;
+
+/* One tensor of an incoming model: its length, its fingerprint (from
+ * tg_fingerprint at registration) and where its bytes start inside the
+ * model's host buffer. */
+typedef struct {
+    uint64_t nbytes;
+    uint64_t fp;
+    uint64_t src_off;
+} tg_tensor_desc;
+
+/* An incoming model.  host_base [pinned host] .. host_base + host_bytes is
+ * the model's image in the Model Cache; tensors [host] has n_tensors rows in
+ * the model's canonical tensor order. */
+typedef struct {
+    uint64_t              model_id;
+    const void           *host_base;
+    uint64_t              host_bytes;
+    uint32_t              n_tensors;
+    uint32_t              reserved;   /* must be 0 */
+    const tg_tensor_desc *tensors;
+} tg_model_desc;
+
+/* What will happen to tensor k of the planned model.
+ * kind == TG_OP_REUSE: pool[dst_off .. +nbytes) = pool[src_off .. +nbytes)
+ * kind == TG_OP_H2D  : pool[dst_off .. +nbytes) = host_base[src_off .. +nbytes) */
+typedef struct {
+    uint32_t kind;
+    uint32_t reserved;
+    uint64_t dst_off;
+    uint64_t src_off;
+    uint64_t nbytes;
+} tg_plan_op;
+
+typedef struct {
+    uint64_t capacity;        /* pool size */
+    uint64_t free_bytes;      /* sum of free regions */
+    uint64_t largest_free;    /* longest free region */
+    uint64_t n_regions;       /* Region List length (free + allocated) */
+    uint64_t n_free_regions;
+    uint64_t n_entries;       /* Tensor Mapping rows (active + inactive) */
+    uint64_t n_active;        /* rows that belong to an active model */
+    uint64_t generation;      /* bumped by every commit and release */
+} tg_stats;
+
+/* Durations, in milliseconds, of the device work of the most recent call of
+ * each kind, measured with HIP events on the stream the work ran on.  Only
+ * filled while profiling is on (tg_set_profiling); a field is 0 if that work
+ * has not run since profiling was switched on. */
+typedef struct {
+    float    fingerprint_ms;  /* fingerprint kernel of the last tg_fingerprint */
+    float    compare_ms;      /* compare kernel of the last tg_compare / confirming tg_plan */
+    float    gather_ms;       /* gather kernel of the last tg_assemble */
+    float    h2d_ms;          /* first to last host-to-device copy of the last tg_assemble */
+    float    verify_ms;       /* fingerprint kernel of the last verifying tg_assemble */
+    float    plan_host_ms;    /* host time of the last tg_plan (steady clock) */
+    uint64_t fingerprint_bytes, compare_bytes, gather_bytes, h2d_bytes, verify_bytes;
+    uint32_t h2d_copies;      /* hipMemcpyAsync calls issued by the last tg_assemble */
+    uint32_t reserved;
+} tg_timing;
+
+/*
+ * Pool.  (Section 3.1: one Unified Memory Pool per GPU; Section 3.2: the pool
+ * is a Region List of free / allocated regions in physical order.)
+ *
+ * dev_base [device] is the slab, capacity its length; both must be multiples
+ * of align, and align a power of two >= 16 (256 is the usual choice).  The
+ * library never allocates, frees or touches the slab here; it records the
+ * base so that offsets can be turned into addresses.  *out receives the pool.
+ * TG_ERR_INVALID on null / zero / misaligned arguments.
+ */
+tg_status tg_pool_create(void *dev_base, uint64_t capacity, uint32_t align, tg_pool **out);
+
+/* Frees the pool's metadata.  The slab is not touched.  NULL is accepted. */
+tg_status tg_pool_destroy(tg_pool *pool);
+
+/* Snapshot of the pool's counters.  out [host]. */
+tg_status tg_pool_stats(const tg_pool *pool, tg_stats *out);
+
+/*
+ * Fingerprint.  (Section 3.1: every tensor has a fingerprint that indexes the
+ * Tensor Mapping.  The function: with gamma = 0x9E3779B97F4A7C15 and
+ * SM(x) = SplitMix64's output for the not-yet-advanced state x,
+ *     F = sum over i of SM(w_i XOR i*gamma)   (mod 2^64)
+ * over the little-endian 64-bit words w_i of the extent, i from 0, bytes past
+ * the end reading as zero; the empty extent has F = 0.)
+ *
+ * spans [host] has n rows whose ptr fields are [device] addresses (pinned
+ * host memory may be passed by its device mapping).  One kernel launch on
+ * `stream` covers all spans; the call waits for it and writes out_fp[0..n)
+ * [host].  n == 0 succeeds and does nothing.  TG_ERR_INVALID for a null
+ * array, a null ptr with nbytes > 0, or a ptr that is not 16-byte aligned.
+ */
+tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream);
+
+/*
+ * Bytewise comparison of n pairs of extents in one launch on `stream`;
+ * out_differs[i] [host] is 0 when pair i holds identical bytes and 1
+ * otherwise.  (The confirmation step behind a fingerprint hit; the paper
+ * treats fingerprints as unique, Section 3.1.)  The call waits for the kernel.
+ */
+tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, void *stream);
+
+/*
+ * Plan the load of `model` into `pool`.  (Section 3.1: search the Tensor
+ * Mapping for the model's tensors; Section 3.2: best-fit allocation.)
+ *
+ *  match    key (fp, nbytes) against the tensors resident when the call
+ *           starts (active or retained); among equal keys the lowest pool
+ *           offset wins.  With TG_PLAN_CONFIRM every candidate is compared
+ *           with the incoming bytes (read from host_base through its device
+ *           mapping by the compare kernel on `stream`) and candidates whose
+ *           bytes differ are dropped.  A tensor with a surviving candidate is
+ *           a TG_OP_REUSE, any other a TG_OP_H2D.
+ *  allocate every tensor gets a fresh slot of roundup(nbytes, align) bytes:
+ *           largest slot first (ties: lower index first), each into the
+ *           smallest free region that holds it (ties: lowest offset), at the
+ *           region's low end.
+ *
+ * The pool is not modified.  *out receives a plan bound to the pool's current
+ * generation.  TG_ERR_INVALID: null arguments, n_tensors == 0, a zero-length
+ * tensor, src_off + nbytes > host_bytes, model_id active in the pool.
+ * TG_ERR_NOSPACE: some tensor has no free region that holds it.
+ * `stream` is used only with TG_PLAN_CONFIRM.
+ */
+tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
+                  tg_load_plan **out);
+
+/* Rows of the plan, one per tensor in the model's order, and byte totals:
+ * reused_bytes + transfer_bytes == sum of nbytes.  *ops points into the plan
+ * and lives until tg_plan_free.  Any out pointer may be NULL. */
+tg_status tg_plan_ops(const tg_load_plan *plan, const tg_plan_op **ops, uint32_t *n,
+                      uint64_t *reused_bytes, uint64_t *transfer_bytes);
+
+void tg_plan_free(tg_load_plan *plan);
+
+/*
+ * Carry out a plan.  (Section 3.1: load the missing tensors, update the
+ * Tensor Mapping, return the GPU address of every tensor; Section 4: tensor
+ * transfers are grouped into large copies.)
+ *
+ * One gather kernel on stream_gather copies every reused tensor into its
+ * slot; at the same time the missing tensors are copied from the model's
+ * pinned host buffer with hipMemcpyAsync on stream_h2d (copies that are
+ * adjacent on both sides are merged into one).  The call waits for both
+ * streams, then commits: slots become allocated regions, one active Tensor
+ * Mapping row per tensor is added, the generation advances.
+ * out_dev_ptrs [host], if not NULL, receives n_tensors [device] addresses.
+ * With TG_ASSEMBLE_VERIFY the slots are fingerprinted (one launch on
+ * stream_gather) before committing and TG_ERR_CORRUPT is returned, without
+ * committing, if any differs from its descriptor.
+ * TG_ERR_STALE if the pool's generation is not the plan's.  A plan can be
+ * assembled once.  The two streams may be the same stream.
+ */
+tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *stream_gather,
+                      void *stream_h2d, void **out_dev_ptrs);
+
+/*
+ * Commit a plan's metadata without enqueuing any copy, for a caller that
+ * fills the slots itself (or only wants the bookkeeping).  Same checks and
+ * same effect on the Region List and Tensor Mapping as tg_assemble.
+ */
+tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs);
+
+/*
+ * The model instance ends.  (Section 3.1: tensors of inactive models stay
+ * resident and reusable until evicted.)  flags == 0 marks the model's rows
+ * inactive; their bytes stay and keep matching.  TG_RELEASE_EVICT removes the
+ * rows and frees their regions, merging each with free neighbours.
+ * TG_ERR_NOTFOUND if the pool holds nothing of model_id.
+ */
+tg_status tg_release(tg_pool *pool, uint64_t model_id, uint32_t flags);
+
+/*
+ * Bytes of `model` that a load would not have to transfer: the sum of nbytes
+ * over tensors whose key is resident (S' of the load-time estimate, Eq. 3;
+ * the quantity the affinity scheduler of Section 3.4 asks each worker for).
+ * est_load_s, if not NULL, receives (S - S') / link_bytes_per_s.
+ */
+tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double link_bytes_per_s,
+                        uint64_t *reuse_bytes, double *est_load_s);
+
+/*
+ * Launch shape of the three streaming kernels.  *_unroll is the number of
+ * independent 128-bit loads a lane issues per tile (2, 4, 8 or 16; a tile is
+ * 256 lanes x 16 B x unroll); *_wgs_per_cu is the number of 256-lane
+ * workgroups launched per compute unit.  h2d_kernel_max_bytes > 0 lets missing
+ * tensors up to that size be fetched by the gather kernel through the pinned
+ * buffer's device mapping instead of one copy-engine call each.  The defaults
+ * are the measured optimum on MI355X; results never depend on these values.
+ */
+typedef struct {
+    uint32_t fingerprint_unroll, fingerprint_wgs_per_cu;
+    uint32_t gather_unroll, gather_wgs_per_cu;
+    uint32_t compare_unroll, compare_wgs_per_cu;
+    uint64_t h2d_kernel_max_bytes;
+} tg_tuning;
+tg_status tg_set_tuning(const tg_tuning *t);
+tg_status tg_get_tuning(tg_tuning *out);
+
+/* Profiling switch and read-out (see tg_timing). */
+void      tg_set_profiling(int on);
+tg_status tg_last_timing(tg_timing *out);
+
+/* Frees the library's device and pinned scratch.  Safe to call twice. */
+void tg_shutdown(void);
+
+/* Static, human-readable name of a status. */
+const char *tg_strerror(tg_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TANGRAM_H */

@@ -1,0 +1,574 @@
+// C ABI of the Load path (see include/tangram.h): argument checks, descriptor
+// tables, kernel launches, the host-to-device side stream and commit.
+#include "../../include/tangram.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "kernels.hip.h"
+#include "reuse_store.h"
+
+struct tg_pool { tg::ReuseStore store; tg_pool(uint64_t b, uint64_t c, uint32_t a) : store(b, c, a) {} };
+struct tg_load_plan { tg::Plan plan; std::vector<tg_plan_op> rows; };
+
+namespace {
+
+using tgk::u32;
+using tgk::u64;
+
+#define TG_HIP(call) do { if ((call) != hipSuccess) { (void)hipGetLastError(); return TG_ERR_HIP; } } while (0)
+
+// Loads in flight per lane (U) and resident workgroups per compute unit for
+// each kernel.  Chosen by measurement on MI355X; see tg_set_tuning.
+tg_tuning g_tune = {8, 4, 8, 8, 8, 8, 0};
+
+bool g_profiling = false;
+tg_timing g_timing = {};
+
+// Library-owned scratch: one pinned staging buffer and one device buffer that
+// hold a launch's descriptor table, tile prefix and result words.
+struct Scratch {
+    std::mutex mu;
+    void *h = nullptr, *d = nullptr;
+    size_t cap = 0;
+    int cu_count = 0;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+
+    tg_status ensure(size_t bytes) {
+        if (cu_count == 0) {
+            int dev = 0;
+            TG_HIP(hipGetDevice(&dev));
+            hipDeviceProp_t prop;
+            TG_HIP(hipGetDeviceProperties(&prop, dev));
+            cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+            for (auto &e : ev) TG_HIP(hipEventCreate(&e));
+        }
+        if (bytes <= cap) return TG_OK;
+        size_t want = std::max<size_t>(bytes * 2, size_t(1) << 20);
+        release_buffers();
+        if (hipHostMalloc(&h, want, hipHostMallocDefault) != hipSuccess) { h = nullptr; (void)hipGetLastError(); return TG_ERR_NOMEM; }
+        if (hipMalloc(&d, want) != hipSuccess) { (void)hipHostFree(h); h = d = nullptr; (void)hipGetLastError(); return TG_ERR_NOMEM; }
+        cap = want;
+        return TG_OK;
+    }
+    void release_buffers() {
+        if (h) (void)hipHostFree(h);
+        if (d) (void)hipFree(d);
+        h = d = nullptr;
+        cap = 0;
+    }
+    void shutdown() {
+        release_buffers();
+        for (auto &e : ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
+        cu_count = 0;
+    }
+} g_scratch;
+
+size_t align_up(size_t n, size_t a) { return (n + a - 1) / a * a; }
+
+// Layout of one launch's table inside the scratch buffers.
+struct TableLayout {
+    size_t desc_off, prefix_off, result_off, total;
+};
+TableLayout table_layout(size_t n, size_t desc_size, size_t result_size) {
+    TableLayout L;
+    L.desc_off = 0;
+    L.prefix_off = align_up(n * desc_size, 256);
+    L.result_off = L.prefix_off + align_up((n + 1) * sizeof(u32), 256);
+    L.total = L.result_off + align_up(n * result_size, 256);
+    return L;
+}
+
+// prefix[s] = number of tiles before extent s.  False if the count overflows.
+bool fill_prefix(u32 *prefix, const u64 *nbytes, size_t stride_words, size_t n, u64 tile) {
+    u64 acc = 0;
+    for (size_t s = 0; s < n; ++s) {
+        prefix[s] = u32(acc);
+        acc += (nbytes[s * stride_words] + tile - 1) / tile;
+        if (acc >= (u64(1) << 32) - 1) return false;
+    }
+    prefix[n] = u32(acc);
+    return true;
+}
+
+u32 grid_for(u32 total_tiles, u32 wgs_per_cu) {
+    const u64 resident = u64(g_scratch.cu_count) * std::max<u32>(1, wgs_per_cu);
+    return u32(std::max<u64>(1, std::min<u64>(total_tiles, resident)));
+}
+
+u32 pick_u(u32 u) { return u >= 16 ? 16 : u >= 8 ? 8 : u >= 4 ? 4 : 2; }
+
+#define TG_FOR_U(U, STMT)                              \
+    switch (U) {                                       \
+        case 16: { constexpr int kU = 16; STMT; break; } \
+        case 8:  { constexpr int kU = 8;  STMT; break; } \
+        case 4:  { constexpr int kU = 4;  STMT; break; } \
+        default: { constexpr int kU = 2;  STMT; break; } \
+    }
+
+u64 tile_for(u32 U) { return u64(tgk::kThreads) * 16 * U; }
+
+// ---- fingerprint over device-visible spans; scratch lock held by the caller
+tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipStream_t st,
+                             float *ms_out, uint64_t *bytes_out) {
+    const u32 U = pick_u(g_tune.fingerprint_unroll);
+    const TableLayout L = table_layout(n, sizeof(tgk::Span), sizeof(u64));
+    tg_status rc = g_scratch.ensure(L.total);
+    if (rc != TG_OK) return rc;
+    char *h = static_cast<char *>(g_scratch.h), *d = static_cast<char *>(g_scratch.d);
+    tgk::Span *hs = reinterpret_cast<tgk::Span *>(h + L.desc_off);
+    u64 total_bytes = 0;
+    for (u32 i = 0; i < n; ++i) {
+        hs[i].ptr = u64(reinterpret_cast<uintptr_t>(spans[i].ptr));
+        hs[i].nbytes = spans[i].nbytes;
+        total_bytes += spans[i].nbytes;
+    }
+    u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
+    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, n, tile_for(U))) return TG_ERR_INVALID;
+    const u32 total_tiles = hp[n];
+    u64 *d_out = reinterpret_cast<u64 *>(d + L.result_off);
+    u64 *h_out = reinterpret_cast<u64 *>(h + L.result_off);
+    TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_out, n);
+    if (total_tiles > 0) {
+        const u32 grid = grid_for(total_tiles, g_tune.fingerprint_wgs_per_cu);
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], st));
+        TG_FOR_U(U, hipLaunchKernelGGL(tgk::fingerprint_kernel<kU>, dim3(grid), dim3(tgk::kThreads), 0, st,
+                                       reinterpret_cast<const tgk::Span *>(d + L.desc_off),
+                                       reinterpret_cast<const u32 *>(d + L.prefix_off), n, d_out));
+        TG_HIP(hipGetLastError());
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], st));
+    }
+    TG_HIP(hipMemcpyAsync(h_out, d_out, n * sizeof(u64), hipMemcpyDeviceToHost, st));
+    TG_HIP(hipStreamSynchronize(st));
+    if (g_profiling && ms_out) {
+        float ms = 0.f;
+        if (total_tiles > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
+        *ms_out = ms;
+        if (bytes_out) *bytes_out = total_bytes;
+    }
+    std::memcpy(out_fp, h_out, n * sizeof(u64));
+    return TG_OK;
+}
+
+tg_status compare_locked(const tg_pair *pairs, u32 n, uint32_t *out_differs, hipStream_t st) {
+    const u32 U = pick_u(g_tune.compare_unroll);
+    const TableLayout L = table_layout(n, sizeof(tgk::Pair), sizeof(u64));
+    tg_status rc = g_scratch.ensure(L.total);
+    if (rc != TG_OK) return rc;
+    char *h = static_cast<char *>(g_scratch.h), *d = static_cast<char *>(g_scratch.d);
+    tgk::Pair *hs = reinterpret_cast<tgk::Pair *>(h + L.desc_off);
+    u64 total_bytes = 0;
+    for (u32 i = 0; i < n; ++i) {
+        hs[i].a = u64(reinterpret_cast<uintptr_t>(pairs[i].a));
+        hs[i].b = u64(reinterpret_cast<uintptr_t>(pairs[i].b));
+        hs[i].nbytes = pairs[i].nbytes;
+        total_bytes += pairs[i].nbytes;
+    }
+    u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
+    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Pair) / 8, n, tile_for(U))) return TG_ERR_INVALID;
+    const u32 total_tiles = hp[n];
+    // results are 32-bit flags; the zero kernel clears whole 64-bit words
+    u32 *d_out = reinterpret_cast<u32 *>(d + L.result_off);
+    u32 *h_out = reinterpret_cast<u32 *>(h + L.result_off);
+    TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
+    const u32 words = (n + 1) / 2;
+    hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((words + 255) / 256), dim3(256), 0, st,
+                       reinterpret_cast<u64 *>(d_out), words);
+    if (total_tiles > 0) {
+        const u32 grid = grid_for(total_tiles, g_tune.compare_wgs_per_cu);
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], st));
+        TG_FOR_U(U, hipLaunchKernelGGL(tgk::compare_kernel<kU>, dim3(grid), dim3(tgk::kThreads), 0, st,
+                                       reinterpret_cast<const tgk::Pair *>(d + L.desc_off),
+                                       reinterpret_cast<const u32 *>(d + L.prefix_off), n, d_out));
+        TG_HIP(hipGetLastError());
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], st));
+    }
+    TG_HIP(hipMemcpyAsync(h_out, d_out, n * sizeof(u32), hipMemcpyDeviceToHost, st));
+    TG_HIP(hipStreamSynchronize(st));
+    if (g_profiling) {
+        float ms = 0.f;
+        if (total_tiles > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
+        g_timing.compare_ms = ms;
+        g_timing.compare_bytes = total_bytes;
+    }
+    std::memcpy(out_differs, h_out, n * sizeof(u32));
+    return TG_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+tg_status check_model(const tg_model_desc *m, std::vector<tg::TensorIn> &tensors) {
+    if (!m || !m->tensors || m->n_tensors == 0 || m->reserved != 0) return TG_ERR_INVALID;
+    tensors.resize(m->n_tensors);
+    for (u32 k = 0; k < m->n_tensors; ++k) {
+        const tg_tensor_desc &t = m->tensors[k];
+        if (t.nbytes == 0) return TG_ERR_INVALID;
+        if (t.src_off > m->host_bytes || t.nbytes > m->host_bytes - t.src_off) return TG_ERR_INVALID;
+        tensors[k] = tg::TensorIn{t.nbytes, t.fp, t.src_off};
+    }
+    return TG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+tg_status tg_pool_create(void *dev_base, uint64_t capacity, uint32_t align, tg_pool **out) {
+    if (!dev_base || !out || capacity == 0) return TG_ERR_INVALID;
+    if (align < 16 || (align & (align - 1)) != 0) return TG_ERR_INVALID;
+    const uint64_t base = uint64_t(reinterpret_cast<uintptr_t>(dev_base));
+    if (base % align != 0 || capacity % align != 0) return TG_ERR_INVALID;
+    if (base + capacity < base) return TG_ERR_INVALID;
+    tg_pool *p = new (std::nothrow) tg_pool(base, capacity, align);
+    if (!p) return TG_ERR_NOMEM;
+    *out = p;
+    return TG_OK;
+}
+
+tg_status tg_pool_destroy(tg_pool *pool) {
+    delete pool;
+    return TG_OK;
+}
+
+tg_status tg_pool_stats(const tg_pool *pool, tg_stats *out) {
+    if (!pool || !out) return TG_ERR_INVALID;
+    const tg::Stats s = pool->store.stats();
+    out->capacity = s.capacity;
+    out->free_bytes = s.free_bytes;
+    out->largest_free = s.largest_free;
+    out->n_regions = s.n_regions;
+    out->n_free_regions = s.n_free_regions;
+    out->n_entries = s.n_entries;
+    out->n_active = s.n_active;
+    out->generation = s.generation;
+    return TG_OK;
+}
+
+tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream) {
+    if (n == 0) return TG_OK;
+    if (!spans || !out_fp) return TG_ERR_INVALID;
+    for (u32 i = 0; i < n; ++i) {
+        if (spans[i].nbytes != 0 && !spans[i].ptr) return TG_ERR_INVALID;
+        if (!aligned16(spans[i].ptr)) return TG_ERR_INVALID;
+    }
+    std::vector<uint64_t> tmp;
+    try { tmp.resize(n); } catch (...) { return TG_ERR_NOMEM; }
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
+    const tg_status rc = fingerprint_locked(spans, n, tmp.data(), static_cast<hipStream_t>(stream),
+                                            &g_timing.fingerprint_ms, &g_timing.fingerprint_bytes);
+    if (rc == TG_OK) std::memcpy(out_fp, tmp.data(), n * sizeof(uint64_t));
+    return rc;
+}
+
+tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, void *stream) {
+    if (n == 0) return TG_OK;
+    if (!pairs || !out_differs) return TG_ERR_INVALID;
+    for (u32 i = 0; i < n; ++i) {
+        if (pairs[i].nbytes != 0 && (!pairs[i].a || !pairs[i].b)) return TG_ERR_INVALID;
+        if (!aligned16(pairs[i].a) || !aligned16(pairs[i].b)) return TG_ERR_INVALID;
+    }
+    std::vector<uint32_t> tmp;
+    try { tmp.resize(n); } catch (...) { return TG_ERR_NOMEM; }
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
+    const tg_status rc = compare_locked(pairs, n, tmp.data(), static_cast<hipStream_t>(stream));
+    if (rc == TG_OK) std::memcpy(out_differs, tmp.data(), n * sizeof(uint32_t));
+    return rc;
+}
+
+tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
+                  tg_load_plan **out) {
+    if (!pool || !out) return TG_ERR_INVALID;
+    const auto t0 = std::chrono::steady_clock::now();
+    std::vector<tg::TensorIn> tensors;
+    tg_status rc = check_model(model, tensors);
+    if (rc != TG_OK) return rc;
+    tg::ReuseStore &store = pool->store;
+    if (store.model_active(model->model_id)) return TG_ERR_INVALID;
+    const bool confirm = (flags & TG_PLAN_CONFIRM) != 0;
+    if (confirm && !model->host_base) return TG_ERR_INVALID;
+
+    const size_t n = tensors.size();
+    std::vector<uint64_t> src(n, UINT64_MAX);
+    std::vector<uint64_t> cand;
+    if (!confirm) {
+        // Section 3.1: a tensor found in the Tensor Mapping is reused.
+        for (size_t k = 0; k < n; ++k) {
+            store.candidates(tensors[k].fp, tensors[k].nbytes, cand);
+            if (!cand.empty()) src[k] = cand.front();
+        }
+    } else {
+        // Every candidate of every tensor is compared with the incoming bytes
+        // in one launch; the first candidate (lowest offset) that is equal wins.
+        void *host_dev = nullptr;
+        if (hipHostGetDevicePointer(&host_dev, const_cast<void *>(model->host_base), 0) != hipSuccess) {
+            (void)hipGetLastError();
+            return TG_ERR_INVALID;
+        }
+        std::vector<tg_pair> pairs;
+        std::vector<std::pair<size_t, uint64_t>> who;   // (tensor, candidate offset)
+        for (size_t k = 0; k < n; ++k) {
+            store.candidates(tensors[k].fp, tensors[k].nbytes, cand);
+            for (uint64_t off : cand) {
+                tg_pair p;
+                p.a = reinterpret_cast<const void *>(uintptr_t(store.base() + off));
+                p.b = static_cast<const char *>(host_dev) + tensors[k].src_off;
+                p.nbytes = tensors[k].nbytes;
+                if (!aligned16(p.b)) return TG_ERR_INVALID;
+                pairs.push_back(p);
+                who.push_back({k, off});
+            }
+        }
+        if (!pairs.empty()) {
+            std::vector<uint32_t> differs(pairs.size());
+            std::lock_guard<std::mutex> lock(g_scratch.mu);
+            rc = compare_locked(pairs.data(), u32(pairs.size()), differs.data(), static_cast<hipStream_t>(stream));
+            if (rc != TG_OK) return rc;
+            for (size_t i = 0; i < pairs.size(); ++i)
+                if (!differs[i] && src[who[i].first] == UINT64_MAX) src[who[i].first] = who[i].second;
+        }
+    }
+
+    tg_load_plan *lp = new (std::nothrow) tg_load_plan();
+    if (!lp) return TG_ERR_NOMEM;
+    lp->plan.model_id = model->model_id;
+    lp->plan.host_base = model->host_base;
+    lp->plan.host_bytes = model->host_bytes;
+    const tg::Status ps = store.place(tensors, src, lp->plan);
+    if (ps != tg::OK) { delete lp; return tg_status(ps); }
+    lp->rows.resize(n);
+    for (size_t k = 0; k < n; ++k) {
+        const tg::Op &op = lp->plan.ops[k];
+        lp->rows[k] = tg_plan_op{op.kind, 0u, op.dst_off, op.src_off, op.nbytes};
+    }
+    *out = lp;
+    if (g_profiling)
+        g_timing.plan_host_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return TG_OK;
+}
+
+tg_status tg_plan_ops(const tg_load_plan *plan, const tg_plan_op **ops, uint32_t *n,
+                      uint64_t *reused_bytes, uint64_t *transfer_bytes) {
+    if (!plan) return TG_ERR_INVALID;
+    if (ops) *ops = plan->rows.data();
+    if (n) *n = uint32_t(plan->rows.size());
+    if (reused_bytes) *reused_bytes = plan->plan.reused_bytes;
+    if (transfer_bytes) *transfer_bytes = plan->plan.transfer_bytes;
+    return TG_OK;
+}
+
+void tg_plan_free(tg_load_plan *plan) { delete plan; }
+
+tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
+    if (!pool || !plan) return TG_ERR_INVALID;
+    std::vector<uint64_t> dst;
+    const tg::Status s = pool->store.commit(plan->plan, dst);
+    if (s != tg::OK) return tg_status(s);
+    if (out_dev_ptrs)
+        for (size_t k = 0; k < dst.size(); ++k)
+            out_dev_ptrs[k] = reinterpret_cast<void *>(uintptr_t(pool->store.base() + dst[k]));
+    return TG_OK;
+}
+
+tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *stream_gather,
+                      void *stream_h2d, void **out_dev_ptrs) {
+    if (!pool || !plan) return TG_ERR_INVALID;
+    tg::ReuseStore &store = pool->store;
+    tg::Plan &pl = plan->plan;
+    if (pl.consumed || pl.pool_tag != &store) return TG_ERR_INVALID;
+    if (pl.generation != store.generation()) return TG_ERR_STALE;
+    if (store.model_active(pl.model_id)) return TG_ERR_INVALID;
+    if (pl.transfer_bytes > 0 && !pl.host_base) return TG_ERR_INVALID;
+    hipStream_t sg = static_cast<hipStream_t>(stream_gather), sh = static_cast<hipStream_t>(stream_h2d);
+    const uint64_t base = store.base();
+
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
+
+    // Host-to-device list, in destination order; copies adjacent on both sides
+    // (the slot padding included) are merged into one (Section 4 groups
+    // adjacent tensors into large copies).
+    struct H2D { uint64_t dst, src, len, padded; };
+    std::vector<H2D> h2d;
+    std::vector<tgk::Copy> copies;
+    void *host_dev = nullptr;
+    const uint64_t small = g_tune.h2d_kernel_max_bytes;
+    if (small > 0 && pl.host_base &&
+        hipHostGetDevicePointer(&host_dev, const_cast<void *>(pl.host_base), 0) != hipSuccess) {
+        (void)hipGetLastError();
+        host_dev = nullptr;
+    }
+    for (const tg::Op &op : pl.ops) {
+        if (op.kind == 0) {
+            copies.push_back(tgk::Copy{base + op.dst_off, base + op.src_off, op.nbytes});
+        } else if (host_dev && op.nbytes <= small &&
+                   ((uintptr_t(host_dev) + op.src_off) & 15u) == 0) {
+            // small missing tensors ride in the gather launch, read through the
+            // pinned buffer's device mapping, instead of one DMA call each
+            copies.push_back(tgk::Copy{base + op.dst_off, u64(uintptr_t(host_dev)) + op.src_off, op.nbytes});
+        } else {
+            h2d.push_back(H2D{op.dst_off, op.src_off, op.nbytes, store.round_up(op.nbytes)});
+        }
+    }
+    std::sort(h2d.begin(), h2d.end(), [](const H2D &a, const H2D &b) { return a.dst < b.dst; });
+    std::vector<H2D> merged;
+    for (const H2D &c : h2d) {
+        if (!merged.empty()) {
+            H2D &m = merged.back();
+            if (m.dst + m.padded == c.dst && m.src + m.padded == c.src) {
+                m.len = m.padded + c.len;
+                m.padded += c.padded;
+                continue;
+            }
+        }
+        merged.push_back(c);
+    }
+
+    // ---- gather launch (stream A)
+    u64 gather_bytes = 0;
+    u32 gather_tiles = 0;
+    if (!copies.empty()) {
+        const u32 n = u32(copies.size());
+        const u32 U = pick_u(g_tune.gather_unroll);
+        const TableLayout L = table_layout(n, sizeof(tgk::Copy), 0);
+        tg_status rc = g_scratch.ensure(L.total);
+        if (rc != TG_OK) return rc;
+        char *h = static_cast<char *>(g_scratch.h), *d = static_cast<char *>(g_scratch.d);
+        std::memcpy(h + L.desc_off, copies.data(), n * sizeof(tgk::Copy));
+        u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
+        if (!fill_prefix(hp, &copies[0].nbytes, sizeof(tgk::Copy) / 8, n, tile_for(U))) return TG_ERR_INVALID;
+        gather_tiles = hp[n];
+        for (const auto &c : copies) gather_bytes += c.nbytes;
+        TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, sg));
+        const u32 grid = grid_for(gather_tiles, g_tune.gather_wgs_per_cu);
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], sg));
+        TG_FOR_U(U, hipLaunchKernelGGL(tgk::gather_kernel<kU>, dim3(grid), dim3(tgk::kThreads), 0, sg,
+                                       reinterpret_cast<const tgk::Copy *>(d + L.desc_off),
+                                       reinterpret_cast<const u32 *>(d + L.prefix_off), n));
+        TG_HIP(hipGetLastError());
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], sg));
+    }
+
+    // ---- host-to-device copies (stream B), overlapped with the gather
+    u64 h2d_bytes = 0;
+    if (!merged.empty()) {
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[2], sh));
+        for (const H2D &c : merged) {
+            TG_HIP(hipMemcpyAsync(reinterpret_cast<void *>(uintptr_t(base + c.dst)),
+                                  static_cast<const char *>(pl.host_base) + c.src, c.len,
+                                  hipMemcpyHostToDevice, sh));
+            h2d_bytes += c.len;
+        }
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[3], sh));
+    }
+
+    // ---- join
+    TG_HIP(hipStreamSynchronize(sg));
+    if (sh != sg) TG_HIP(hipStreamSynchronize(sh));
+    if (g_profiling) {
+        float ms = 0.f;
+        if (!copies.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
+        g_timing.gather_ms = ms;
+        g_timing.gather_bytes = gather_bytes;
+        ms = 0.f;
+        if (!merged.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[2], g_scratch.ev[3]));
+        g_timing.h2d_ms = ms;
+        g_timing.h2d_bytes = h2d_bytes;
+        g_timing.h2d_copies = u32(merged.size());
+    }
+
+    // ---- optional integrity check of what now sits in the slots
+    if (flags & TG_ASSEMBLE_VERIFY) {
+        const u32 n = u32(pl.ops.size());
+        std::vector<tg_span> spans(n);
+        std::vector<uint64_t> got(n);
+        for (u32 k = 0; k < n; ++k) {
+            spans[k].ptr = reinterpret_cast<const void *>(uintptr_t(base + pl.ops[k].dst_off));
+            spans[k].nbytes = pl.ops[k].nbytes;
+        }
+        tg_status rc = fingerprint_locked(spans.data(), n, got.data(), sg, &g_timing.verify_ms,
+                                          &g_timing.verify_bytes);
+        if (rc != TG_OK) return rc;
+        for (u32 k = 0; k < n; ++k)
+            if (got[k] != pl.fps[k]) return TG_ERR_CORRUPT;
+    }
+
+    // ---- commit (Section 3.1: update the mapping, return the addresses)
+    std::vector<uint64_t> dst;
+    const tg::Status s = store.commit(pl, dst);
+    if (s != tg::OK) return tg_status(s);
+    if (out_dev_ptrs)
+        for (size_t k = 0; k < dst.size(); ++k)
+            out_dev_ptrs[k] = reinterpret_cast<void *>(uintptr_t(base + dst[k]));
+    return TG_OK;
+}
+
+tg_status tg_release(tg_pool *pool, uint64_t model_id, uint32_t flags) {
+    if (!pool) return TG_ERR_INVALID;
+    return tg_status(pool->store.release(model_id, (flags & TG_RELEASE_EVICT) != 0));
+}
+
+tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double link_bytes_per_s,
+                        uint64_t *reuse_bytes, double *est_load_s) {
+    if (!pool || !reuse_bytes) return TG_ERR_INVALID;
+    std::vector<tg::TensorIn> tensors;
+    const tg_status rc = check_model(model, tensors);
+    if (rc != TG_OK) return rc;
+    if (est_load_s && !(link_bytes_per_s > 0.0)) return TG_ERR_INVALID;
+    const uint64_t reuse = pool->store.reuse_size(tensors);
+    uint64_t total = 0;
+    for (const auto &t : tensors) total += t.nbytes;
+    *reuse_bytes = reuse;
+    // Eq. 3: t_load = (S - S') / B
+    if (est_load_s) *est_load_s = double(total - reuse) / link_bytes_per_s;
+    return TG_OK;
+}
+
+void tg_set_profiling(int on) {
+    g_profiling = on != 0;
+    g_timing = tg_timing{};
+}
+
+tg_status tg_last_timing(tg_timing *out) {
+    if (!out) return TG_ERR_INVALID;
+    *out = g_timing;
+    return TG_OK;
+}
+
+tg_status tg_set_tuning(const tg_tuning *t) {
+    if (!t) return TG_ERR_INVALID;
+    g_tune = *t;
+    return TG_OK;
+}
+
+tg_status tg_get_tuning(tg_tuning *t) {
+    if (!t) return TG_ERR_INVALID;
+    *t = g_tune;
+    return TG_OK;
+}
+
+void tg_shutdown(void) {
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
+    g_scratch.shutdown();
+}
+
+const char *tg_strerror(tg_status s) {
+    switch (s) {
+        case TG_OK: return "ok";
+        case TG_ERR_INVALID: return "invalid argument";
+        case TG_ERR_NOSPACE: return "no space in pool";
+        case TG_ERR_STALE: return "plan is stale";
+        case TG_ERR_NOTFOUND: return "model not found";
+        case TG_ERR_HIP: return "HIP call failed";
+        case TG_ERR_NOMEM: return "out of memory";
+        case TG_ERR_CORRUPT: return "assembled bytes do not match fingerprint";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

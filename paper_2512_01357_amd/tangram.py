@@ -1,0 +1,291 @@
+"""ctypes binding of libtangram.so: the same names as include/tangram.h.
+
+Argument marshalling only -- every step of the Load path (fingerprint, match,
+allocation, gather, host-to-device stream, commit) runs inside the library.
+There is no fallback: if the shared object is missing or fails to load, the
+import of this module's functions raises.
+"""
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtangram.so")
+
+TG_OK = 0
+TG_ERR_INVALID = -1
+TG_ERR_NOSPACE = -2
+TG_ERR_STALE = -3
+TG_ERR_NOTFOUND = -4
+TG_ERR_HIP = -5
+TG_ERR_NOMEM = -6
+TG_ERR_CORRUPT = -7
+
+TG_PLAN_CONFIRM = 1
+TG_ASSEMBLE_VERIFY = 1
+TG_RELEASE_EVICT = 1
+TG_OP_REUSE = 0
+TG_OP_H2D = 1
+
+
+class tg_span(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("nbytes", ctypes.c_uint64)]
+
+
+class tg_pair(ctypes.Structure):
+    _fields_ = [("a", ctypes.c_void_p), ("b", ctypes.c_void_p), ("nbytes", ctypes.c_uint64)]
+
+
+class tg_tensor_desc(ctypes.Structure):
+    _fields_ = [("nbytes", ctypes.c_uint64), ("fp", ctypes.c_uint64), ("src_off", ctypes.c_uint64)]
+
+
+class tg_model_desc(ctypes.Structure):
+    _fields_ = [("model_id", ctypes.c_uint64), ("host_base", ctypes.c_void_p),
+                ("host_bytes", ctypes.c_uint64), ("n_tensors", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32), ("tensors", ctypes.POINTER(tg_tensor_desc))]
+
+
+class tg_plan_op(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+                ("dst_off", ctypes.c_uint64), ("src_off", ctypes.c_uint64),
+                ("nbytes", ctypes.c_uint64)]
+
+
+class tg_stats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in (
+        "capacity", "free_bytes", "largest_free", "n_regions", "n_free_regions",
+        "n_entries", "n_active", "generation")]
+
+
+class tg_timing(ctypes.Structure):
+    _fields_ = ([(n, ctypes.c_float) for n in (
+        "fingerprint_ms", "compare_ms", "gather_ms", "h2d_ms", "verify_ms", "plan_host_ms")]
+        + [(n, ctypes.c_uint64) for n in (
+            "fingerprint_bytes", "compare_bytes", "gather_bytes", "h2d_bytes", "verify_bytes")]
+        + [("h2d_copies", ctypes.c_uint32), ("reserved", ctypes.c_uint32)])
+
+
+class tg_tuning(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in (
+        "fingerprint_unroll", "fingerprint_wgs_per_cu", "gather_unroll", "gather_wgs_per_cu",
+        "compare_unroll", "compare_wgs_per_cu")] + [("h2d_kernel_max_bytes", ctypes.c_uint64)]
+
+
+class TgError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, tg_strerror(status), status))
+
+
+_lib = None
+
+EXPORTS = [
+    "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_fingerprint", "tg_compare",
+    "tg_plan", "tg_plan_ops", "tg_plan_free", "tg_assemble", "tg_commit", "tg_release",
+    "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
+    "tg_shutdown", "tg_strerror",
+]
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "libtangram.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "or `python paper_2512_01357_amd/build.py` first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u32, u64, i32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32
+        P = ctypes.POINTER
+        sig = {
+            "tg_pool_create": ([vp, u64, u32, P(vp)], i32),
+            "tg_pool_destroy": ([vp], i32),
+            "tg_pool_stats": ([vp, P(tg_stats)], i32),
+            "tg_fingerprint": ([P(tg_span), u32, P(u64), vp], i32),
+            "tg_compare": ([P(tg_pair), u32, P(u32), vp], i32),
+            "tg_plan": ([vp, P(tg_model_desc), u32, vp, P(vp)], i32),
+            "tg_plan_ops": ([vp, P(P(tg_plan_op)), P(u32), P(u64), P(u64)], i32),
+            "tg_plan_free": ([vp], None),
+            "tg_assemble": ([vp, vp, u32, vp, vp, P(vp)], i32),
+            "tg_commit": ([vp, vp, P(vp)], i32),
+            "tg_release": ([vp, u64, u32], i32),
+            "tg_reuse_size": ([vp, P(tg_model_desc), ctypes.c_double, P(u64), P(ctypes.c_double)], i32),
+            "tg_set_tuning": ([P(tg_tuning)], i32),
+            "tg_get_tuning": ([P(tg_tuning)], i32),
+            "tg_set_profiling": ([ctypes.c_int], None),
+            "tg_last_timing": ([P(tg_timing)], i32),
+            "tg_shutdown": ([], None),
+            "tg_strerror": ([i32], ctypes.c_char_p),
+        }
+        for name, (args, res) in sig.items():
+            fn = getattr(L, name)
+            fn.argtypes = args
+            fn.restype = res
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != TG_OK:
+        raise TgError(status, where)
+
+
+def tg_strerror(status: int) -> str:
+    return lib().tg_strerror(status).decode()
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    """A torch.cuda.Stream, a raw hipStream_t integer, or None (null stream)."""
+    if stream is None:
+        return ctypes.c_void_p(0)
+    if hasattr(stream, "cuda_stream"):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+# --------------------------------------------------------------------- pool
+def tg_pool_create(dev_base: int, capacity: int, align: int = 256) -> ctypes.c_void_p:
+    out = ctypes.c_void_p()
+    _check(lib().tg_pool_create(ctypes.c_void_p(dev_base), capacity, align, ctypes.byref(out)),
+           "tg_pool_create")
+    return out
+
+
+def tg_pool_destroy(pool) -> None:
+    _check(lib().tg_pool_destroy(pool), "tg_pool_destroy")
+
+
+def tg_pool_stats(pool) -> dict:
+    st = tg_stats()
+    _check(lib().tg_pool_stats(pool, ctypes.byref(st)), "tg_pool_stats")
+    return {n: int(getattr(st, n)) for n, _ in tg_stats._fields_}
+
+
+# ---------------------------------------------------------------- device ops
+def tg_fingerprint(spans: Sequence[Tuple[int, int]], stream=None) -> List[int]:
+    """spans: (device address, nbytes) rows.  Returns their fingerprints."""
+    n = len(spans)
+    arr = (tg_span * max(n, 1))()
+    for i, (ptr, nbytes) in enumerate(spans):
+        arr[i].ptr = ptr
+        arr[i].nbytes = nbytes
+    out = (ctypes.c_uint64 * max(n, 1))()
+    _check(lib().tg_fingerprint(arr, n, out, _stream(stream)), "tg_fingerprint")
+    return [int(out[i]) for i in range(n)]
+
+
+def tg_compare(pairs: Sequence[Tuple[int, int, int]], stream=None) -> List[int]:
+    """pairs: (address a, address b, nbytes) rows.  1 where the bytes differ."""
+    n = len(pairs)
+    arr = (tg_pair * max(n, 1))()
+    for i, (a, b, nbytes) in enumerate(pairs):
+        arr[i].a = a
+        arr[i].b = b
+        arr[i].nbytes = nbytes
+    out = (ctypes.c_uint32 * max(n, 1))()
+    _check(lib().tg_compare(arr, n, out, _stream(stream)), "tg_compare")
+    return [int(out[i]) for i in range(n)]
+
+
+# --------------------------------------------------------------------- model
+class ModelDesc:
+    """Owns the ctypes storage behind a tg_model_desc."""
+
+    def __init__(self, model_id: int, host_base: int, host_bytes: int,
+                 tensors: Sequence[Tuple[int, int, int]]):
+        """tensors: (nbytes, fp, src_off) rows in the model's tensor order."""
+        self.n = len(tensors)
+        self._rows = (tg_tensor_desc * max(self.n, 1))()
+        for k, (nbytes, fp, off) in enumerate(tensors):
+            self._rows[k].nbytes = nbytes
+            self._rows[k].fp = fp
+            self._rows[k].src_off = off
+        self.c = tg_model_desc(model_id, host_base, host_bytes, self.n, 0,
+                               ctypes.cast(self._rows, ctypes.POINTER(tg_tensor_desc)))
+        self.model_id = model_id
+        self.nbytes = sum(t[0] for t in tensors)
+
+
+def tg_plan(pool, model: ModelDesc, flags: int = 0, stream=None) -> ctypes.c_void_p:
+    out = ctypes.c_void_p()
+    _check(lib().tg_plan(pool, ctypes.byref(model.c), flags, _stream(stream), ctypes.byref(out)),
+           "tg_plan")
+    return out
+
+
+def tg_plan_ops(plan) -> Tuple[List[Tuple[int, int, int, int]], int, int]:
+    """((kind, dst_off, src_off, nbytes) rows, reused_bytes, transfer_bytes)."""
+    ops = ctypes.POINTER(tg_plan_op)()
+    n = ctypes.c_uint32()
+    reused = ctypes.c_uint64()
+    transfer = ctypes.c_uint64()
+    _check(lib().tg_plan_ops(plan, ctypes.byref(ops), ctypes.byref(n), ctypes.byref(reused),
+                             ctypes.byref(transfer)), "tg_plan_ops")
+    rows = [(int(ops[k].kind), int(ops[k].dst_off), int(ops[k].src_off), int(ops[k].nbytes))
+            for k in range(n.value)]
+    return rows, int(reused.value), int(transfer.value)
+
+
+def tg_plan_free(plan) -> None:
+    lib().tg_plan_free(plan)
+
+
+def tg_assemble(pool, plan, n_tensors: int, flags: int = 0, stream_gather=None,
+                stream_h2d=None) -> List[int]:
+    out = (ctypes.c_void_p * max(n_tensors, 1))()
+    _check(lib().tg_assemble(pool, plan, flags, _stream(stream_gather), _stream(stream_h2d), out),
+           "tg_assemble")
+    return [int(out[k] or 0) for k in range(n_tensors)]
+
+
+def tg_commit(pool, plan, n_tensors: int) -> List[int]:
+    out = (ctypes.c_void_p * max(n_tensors, 1))()
+    _check(lib().tg_commit(pool, plan, out), "tg_commit")
+    return [int(out[k] or 0) for k in range(n_tensors)]
+
+
+def tg_release(pool, model_id: int, flags: int = 0) -> None:
+    _check(lib().tg_release(pool, model_id, flags), "tg_release")
+
+
+def tg_reuse_size(pool, model: ModelDesc, link_bytes_per_s: Optional[float] = None
+                  ) -> Tuple[int, Optional[float]]:
+    reuse = ctypes.c_uint64()
+    if link_bytes_per_s is None:
+        _check(lib().tg_reuse_size(pool, ctypes.byref(model.c), 0.0, ctypes.byref(reuse), None),
+               "tg_reuse_size")
+        return int(reuse.value), None
+    est = ctypes.c_double()
+    _check(lib().tg_reuse_size(pool, ctypes.byref(model.c), link_bytes_per_s, ctypes.byref(reuse),
+                               ctypes.byref(est)), "tg_reuse_size")
+    return int(reuse.value), float(est.value)
+
+
+# ------------------------------------------------------------ tuning, timing
+def tg_get_tuning() -> dict:
+    t = tg_tuning()
+    _check(lib().tg_get_tuning(ctypes.byref(t)), "tg_get_tuning")
+    return {n: int(getattr(t, n)) for n, _ in tg_tuning._fields_}
+
+
+def tg_set_tuning(**kw) -> None:
+    cur = tg_get_tuning()
+    cur.update(kw)
+    t = tg_tuning(**cur)
+    _check(lib().tg_set_tuning(ctypes.byref(t)), "tg_set_tuning")
+
+
+def tg_set_profiling(on: bool) -> None:
+    lib().tg_set_profiling(1 if on else 0)
+
+
+def tg_last_timing() -> dict:
+    t = tg_timing()
+    _check(lib().tg_last_timing(ctypes.byref(t)), "tg_last_timing")
+    return {n: getattr(t, n) for n, _ in tg_timing._fields_ if n != "reserved"}
+
+
+def tg_shutdown() -> None:
+    lib().tg_shutdown()

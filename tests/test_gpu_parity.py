@@ -1,0 +1,387 @@
+"""GPU parity: the HIP path against the CPU oracle, through the C ABI.
+
+Integer and byte work: everything is compared bit for bit.
+"""
+import os
+import random
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+import oracle  # noqa: E402
+from oracle import ReuseStoreOracle  # noqa: E402
+from paper_2512_01357_amd import synth  # noqa: E402
+from paper_2512_01357_amd import tangram as tg  # noqa: E402
+from paper_2512_01357_amd.loader import ReusePool  # noqa: E402
+from paper_2512_01357_amd.runner import WorkloadRunner  # noqa: E402
+from recipes import build, read_pairs  # noqa: E402
+from test_oracle_fingerprint import colliding_pair  # noqa: E402
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[gpu-test] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev_bytes(data: bytes, pad: int = 64) -> torch.Tensor:
+    """data on the device, followed by `pad` bytes of 0xA5 that must not be read."""
+    buf = np.frombuffer(data + b"\xA5" * pad, dtype=np.uint8).copy()
+    return torch.from_numpy(buf).to(DEV)
+
+
+def random_bytes(rnd: random.Random, n: int) -> bytes:
+    return np.random.default_rng(rnd.getrandbits(32)).integers(0, 256, n, dtype=np.uint8).tobytes()
+
+
+TILE_U8 = 256 * 16 * 8
+LENGTHS = [0, 1, 7, 8, 9, 15, 16, 17, 31, 4095, 4096, 4097, TILE_U8 - 1, TILE_U8, TILE_U8 + 1,
+           TILE_U8 + 16, 3 * TILE_U8 + 4096 + 5, 10 * TILE_U8, (1 << 20) + 24, 5 * (1 << 20) + 13]
+
+
+@pytest.mark.parametrize("unroll", [2, 4, 8, 16])
+def test_fingerprint_matches_oracle_on_ragged_lengths(unroll):
+    say("fingerprint ragged lengths unroll=%d" % unroll)
+    old = tg.tg_get_tuning()
+    tg.tg_set_tuning(fingerprint_unroll=unroll)
+    try:
+        rnd = random.Random(unroll)
+        datas = [random_bytes(rnd, n) for n in LENGTHS]
+        bufs = [dev_bytes(d) for d in datas]
+        torch.cuda.synchronize()
+        spans = [(b.data_ptr(), len(d)) for b, d in zip(bufs, datas)]
+        got = tg.tg_fingerprint(spans)
+        want = [oracle.fingerprint(d) for d in datas]
+        assert got == want
+        # one span at a time gives the same values
+        for sp, w in zip(spans[:8], want[:8]):
+            assert tg.tg_fingerprint([sp]) == [w]
+    finally:
+        tg.tg_set_tuning(**old)
+
+
+def test_fingerprint_golden_recipes_and_empty_call():
+    say("fingerprint golden recipes")
+    pairs = read_pairs(os.path.join(HERE, "golden", "fingerprints.txt"))
+    datas = [build(r) for r, _ in pairs]
+    bufs = [dev_bytes(d) for d in datas]
+    torch.cuda.synchronize()
+    got = tg.tg_fingerprint([(b.data_ptr(), len(d)) for b, d in zip(bufs, datas)])
+    assert got == [v for _, v in pairs]
+    assert tg.tg_fingerprint([]) == []
+
+
+def test_fingerprint_many_small_spans_and_small_grid():
+    say("fingerprint many spans")
+    rnd = random.Random(99)
+    blob = random_bytes(rnd, 3 << 20)
+    buf = dev_bytes(blob)
+    torch.cuda.synchronize()
+    spans, want = [], []
+    at = 0
+    while at + 70000 < len(blob) and len(spans) < 700:
+        n = rnd.choice([16, 48, 512, 4096, 8192, 12288, 40000, 66000])
+        spans.append((buf.data_ptr() + at, n))
+        want.append(oracle.fingerprint(blob[at:at + n]))
+        at += (n + 15) // 16 * 16
+    old = tg.tg_get_tuning()
+    try:
+        for wgs in (1, 4, 16):
+            tg.tg_set_tuning(fingerprint_wgs_per_cu=wgs)
+            assert tg.tg_fingerprint(spans) == want
+    finally:
+        tg.tg_set_tuning(**old)
+
+
+def test_fingerprint_rejects_bad_arguments():
+    buf = dev_bytes(bytes(4096))
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_fingerprint([(buf.data_ptr() + 8, 64)])
+    assert e.value.status == tg.TG_ERR_INVALID
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_fingerprint([(0, 64)])
+    assert e.value.status == tg.TG_ERR_INVALID
+
+
+def test_fingerprint_on_a_stream_and_single_bit_flip():
+    say("fingerprint stream + bit flip")
+    rnd = random.Random(5)
+    data = bytearray(random_bytes(rnd, (2 << 20) + 40))
+    st = torch.cuda.Stream()
+    buf = dev_bytes(bytes(data))
+    torch.cuda.synchronize()
+    base = tg.tg_fingerprint([(buf.data_ptr(), len(data))], st)[0]
+    assert base == oracle.fingerprint(bytes(data))
+    for pos in (0, 12345, len(data) - 1):
+        data[pos] ^= 0x04
+        b2 = dev_bytes(bytes(data))
+        torch.cuda.synchronize()
+        f = tg.tg_fingerprint([(b2.data_ptr(), len(data))], st)[0]
+        assert f == oracle.fingerprint(bytes(data)) and f != base
+        data[pos] ^= 0x04
+
+
+@pytest.mark.parametrize("unroll", [2, 8, 16])
+def test_compare_matches_oracle(unroll):
+    say("compare unroll=%d" % unroll)
+    old = tg.tg_get_tuning()
+    tg.tg_set_tuning(compare_unroll=unroll)
+    try:
+        rnd = random.Random(7 + unroll)
+        pairs, want, keep = [], [], []
+        for n in LENGTHS[1:]:
+            a = bytearray(random_bytes(rnd, n))
+            for flip in (None, 0, n // 2, n - 1):
+                b = bytearray(a)
+                if flip is not None:
+                    b[flip] ^= 0x80
+                ta, tb = dev_bytes(bytes(a)), dev_bytes(bytes(b))
+                keep += [ta, tb]
+                pairs.append((ta.data_ptr(), tb.data_ptr(), n))
+                want.append(0 if oracle.bytes_equal(bytes(a), bytes(b)) else 1)
+        torch.cuda.synchronize()
+        assert tg.tg_compare(pairs) == want
+        assert tg.tg_compare([]) == []
+        # zero-length pair is equal
+        assert tg.tg_compare([(keep[0].data_ptr(), keep[1].data_ptr(), 0)]) == [0]
+    finally:
+        tg.tg_set_tuning(**old)
+
+
+def pinned(data: np.ndarray) -> torch.Tensor:
+    t = torch.empty(max(data.size, 256), dtype=torch.uint8, pin_memory=True)
+    t[:data.size].copy_(torch.from_numpy(data))
+    return t
+
+
+def pack(tensors, align=256):
+    offs, at = [], 0
+    for t in tensors:
+        offs.append(at)
+        at += (len(t) + align - 1) // align * align
+    host = np.zeros(max(at, align), dtype=np.uint8)
+    for t, o in zip(tensors, offs):
+        host[o:o + len(t)] = np.frombuffer(t, dtype=np.uint8)
+    return host, offs
+
+
+class Both:
+    """The library and the oracle driven side by side on the same bytes."""
+
+    def __init__(self, capacity, align=256):
+        self.pool = ReusePool(capacity, align, DEV)
+        self.store = ReuseStoreOracle(capacity, align)
+
+    def load(self, model_id, tensors, confirm=False, verify=False, fps=None):
+        host, offs = pack(tensors, self.pool.align)
+        hp = pinned(host)
+        sizes = [len(t) for t in tensors]
+        reg = self.pool.register(model_id, hp, offs, sizes, fps=fps)
+        want_fps = [oracle.fingerprint(t) for t in tensors]
+        if fps is None:
+            assert reg.fps == want_fps
+        rows = [(n, f, o) for n, f, o in zip(sizes, reg.fps, offs)]
+        oplan = self.store.plan(model_id, rows, host, confirm)
+        ptrs, info = self.pool.load(reg, confirm=confirm, verify=verify)
+        assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops]
+        assert info["reused_bytes"] == oplan.reused_bytes
+        assert info["transfer_bytes"] == oplan.transfer_bytes
+        dsts = self.store.assemble(oplan, host)
+        assert ptrs == [self.pool.base + d for d in dsts]
+        self.check_image()
+        return oplan
+
+    def check_image(self):
+        """Every resident slot holds exactly the oracle's bytes."""
+        for e in self.store.entries:
+            got = self.pool.slab[e.off:e.off + e.nbytes].cpu().numpy()
+            assert got.tobytes() == self.store.image[e.off].tobytes(), (e.off, e.nbytes)
+        a, b = self.pool.stats(), self.store.stats()
+        for k, v in b.items():
+            assert a[k] == v, k
+
+    def release(self, model_id, evict=False):
+        self.pool.release(model_id, evict)
+        self.store.release(model_id, evict)
+
+    def close(self):
+        self.pool.close()
+
+
+@pytest.mark.parametrize("gather_unroll", [2, 8, 16])
+def test_load_small_models_ragged_sizes(gather_unroll):
+    say("assemble ragged sizes gather_unroll=%d" % gather_unroll)
+    old = tg.tg_get_tuning()
+    tg.tg_set_tuning(gather_unroll=gather_unroll)
+    try:
+        rnd = random.Random(31 + gather_unroll)
+        b = Both(64 << 20)
+        sizes = [1, 7, 16, 24, 255, 256, 257, 4096, 5000, TILE_U8 - 16, TILE_U8, TILE_U8 + 8,
+                 3 * TILE_U8 + 4096 + 5, (1 << 20) + 24, 3 * (1 << 20) + 1]
+        a = [random_bytes(rnd, n) for n in sizes]
+        b.load(1, a)
+        b.release(1)
+        # second model: mix of hits (copied device to device) and misses
+        m2 = [a[i] if i % 3 else random_bytes(rnd, sizes[i]) for i in range(len(sizes))]
+        plan = b.load(2, m2, verify=True)
+        assert sum(1 for op in plan.ops if op.kind == 0) == sum(1 for i in range(len(sizes)) if i % 3)
+        b.release(1, evict=True)
+        # third model lands in the holes model 1 left
+        m3 = [m2[i] for i in (14, 13, 3, 0)] + [random_bytes(rnd, 70000)]
+        b.load(3, m3, verify=True)
+        b.release(2, evict=True)
+        b.release(3)
+        b.check_image()
+        b.close()
+    finally:
+        tg.tg_set_tuning(**old)
+
+
+def test_small_missing_tensors_through_the_gather_kernel():
+    say("small H2D via kernel")
+    old = tg.tg_get_tuning()
+    tg.tg_set_tuning(h2d_kernel_max_bytes=65536)
+    try:
+        rnd = random.Random(41)
+        b = Both(32 << 20)
+        a = [random_bytes(rnd, n) for n in (16, 512, 4096, 65536, 65537, 1 << 20, 24, 8192)]
+        b.load(1, a, verify=True)
+        b.release(1)
+        m2 = [a[0], random_bytes(rnd, 512), a[5], random_bytes(rnd, 100000), random_bytes(rnd, 7)]
+        b.load(2, m2, verify=True)
+        b.close()
+    finally:
+        tg.tg_set_tuning(**old)
+
+
+def test_confirm_demotes_a_constructed_collision():
+    say("confirm vs collision")
+    x, y = colliding_pair(seed=33, words=64)
+    rnd = random.Random(43)
+    other = random_bytes(rnd, 4096)
+    b = Both(1 << 20)
+    b.load(1, [x, other])
+    b.release(1)
+    # without confirmation the colliding tensor is (wrongly) taken as resident:
+    # the oracle says the same, and the bytes in the slot are x's, not y's
+    plan = b.load(2, [y, other], confirm=False)
+    assert [op.kind for op in plan.ops] == [0, 0]
+    b.release(2, evict=True)
+    # with confirmation it is transferred
+    plan = b.load(3, [y, other], confirm=True, verify=True)
+    assert [op.kind for op in plan.ops] == [1, 0]
+    got = b.pool.slab[plan.ops[0].dst_off:plan.ops[0].dst_off + len(y)].cpu().numpy().tobytes()
+    assert got == y
+    b.close()
+
+
+def test_verify_detects_a_wrong_fingerprint_and_leaves_the_pool_alone():
+    say("verify flag")
+    rnd = random.Random(47)
+    b = Both(1 << 20)
+    a = [random_bytes(rnd, 4096), random_bytes(rnd, 1000)]
+    good = [oracle.fingerprint(t) for t in a]
+    host, offs = pack(a)
+    hp = pinned(host)
+    reg = b.pool.register(1, hp, offs, [4096, 1000], fps=[good[0], good[1] ^ 1])
+    before = b.pool.stats()
+    with pytest.raises(tg.TgError) as e:
+        b.pool.load(reg, verify=True)
+    assert e.value.status == tg.TG_ERR_CORRUPT
+    assert b.pool.stats() == before
+    b.close()
+
+
+def test_stale_and_no_space_on_the_device_path():
+    rnd = random.Random(53)
+    pool = ReusePool(4096, 256, DEV)
+    t = [random_bytes(rnd, 1024)]
+    host, offs = pack(t)
+    hp = pinned(host)
+    reg1 = pool.register(1, hp, offs, [1024])
+    reg2 = pool.register(2, hp, offs, [1024])
+    p1 = tg.tg_plan(pool.pool, reg1.desc)
+    p2 = tg.tg_plan(pool.pool, reg2.desc)
+    tg.tg_assemble(pool.pool, p1, 1, 0, pool.stream_gather, pool.stream_h2d)
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_assemble(pool.pool, p2, 1, 0, pool.stream_gather, pool.stream_h2d)
+    assert e.value.status == tg.TG_ERR_STALE
+    tg.tg_plan_free(p1)
+    tg.tg_plan_free(p2)
+    big = [random_bytes(rnd, 4096)]
+    host2, offs2 = pack(big)
+    reg3 = pool.register(3, pinned(host2), offs2, [4096])
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_plan(pool.pool, reg3.desc)
+    assert e.value.status == tg.TG_ERR_NOSPACE
+    pool.close()
+
+
+def run_workload_both(w, sample_check=None):
+    """Replays a workload on the library and on the oracle (with images)."""
+    r = WorkloadRunner(w, DEV, gen_device=DEV, log=say)
+    store = ReuseStoreOracle(w.pool_bytes, w.align)
+    host_np = {}
+
+    def rows(name):
+        reg = r.materialise(name)
+        host_np[name] = r.host[name].numpy()
+        spec = w.models[name]
+        want = [oracle.fingerprint(host_np[name][o:o + t.nbytes]) for t, o in zip(spec.tensors, reg.offs)]
+        assert reg.fps == want, "fingerprints of %s" % name
+        return [(n, f, o) for n, f, o in zip(reg.sizes, reg.fps, reg.offs)]
+
+    def load(name):
+        rws = rows(name)
+        oplan = store.plan(w.models[name].model_id, rws, host_np[name])
+        ptrs, info = r.load(name, verify=True)
+        assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops]
+        dsts = store.assemble(oplan, host_np[name])
+        assert ptrs == [r.pool.base + d for d in dsts]
+        for op, (n, f, o) in zip(oplan.ops, rws):
+            got = r.pool.pool and r.pool.slab[op.dst_off:op.dst_off + n].cpu().numpy()
+            assert got.tobytes() == store.image[op.dst_off].tobytes()
+            assert got.tobytes() == host_np[name][o:o + n].tobytes()
+        return oplan
+
+    for act in w.setup:
+        if act[0] == "load":
+            load(act[1])
+        else:
+            r.release(act[1], act[2])
+            store.release(w.models[act[1]].model_id, act[2])
+    plans = {}
+    for name in w.loads:
+        plans[name] = load(name)
+        a, b = r.pool.stats(), store.stats()
+        for k, v in b.items():
+            assert a[k] == v, k
+        r.release(name, True)
+        store.release(w.models[name].model_id, True)
+    r.close()
+    return plans
+
+
+def test_workload_tiny_gpt_pair():
+    say("workload tiny")
+    w = synth.workload_tiny()
+    plans = run_workload_both(w)
+    assert sum(1 for op in plans["B"].ops if op.kind == 0) == 39
+
+
+def test_workload_gpt_1_3b():
+    say("workload gpt1b")
+    w = synth.workload_gpt1b()
+    plans = run_workload_both(w)
+    p = plans["M"]
+    assert p.reused_bytes + p.transfer_bytes == w.models["M"].nbytes
+    assert 0.45 < p.reused_bytes / w.models["M"].nbytes < 0.60
