@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the Load path on one MI355X.
+
+A step is one whole load of a model into a pool that already holds its
+sibling(s): tg_plan (match + best-fit), tg_assemble (gather kernel for the
+reused tensors overlapped with the host-to-device stream for the missing
+ones, then a fingerprint launch over every assembled slot, then commit) and
+tg_release with eviction, which puts the pool back as it was.  Steps cycle
+through the workload's models (for the 7B family: variants v1, v2, v3).
+
+Prints one JSON line: effective load GB/s (model bytes / step time), with the
+roofline of the dominant kernel, the other kernels' figures, the host-link
+figure and the CPU oracle's rate on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import threading
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def measure_link_peak(torch, nbytes=2 << 30, reps=3):
+    """GB/s of one large pinned-to-device hipMemcpyAsync (the host link's
+    measured peak on this machine, same run): a one-tensor model loaded into an
+    empty pool through the library, timed by its HIP events."""
+    from paper_2512_01357_amd import tangram as tg
+    from paper_2512_01357_amd.loader import HostArena, RegisteredModel, ReusePool
+    arena = HostArena(nbytes)
+    arena.tensor.fill_(1)
+    pool = ReusePool(nbytes, 256, "cuda:0")
+    reg = RegisteredModel(1, arena, [0], [nbytes], [0])
+    tg.tg_set_profiling(True)
+    best = 0.0
+    for _ in range(reps + 1):
+        pool.load(reg)
+        t = tg.tg_last_timing()
+        pool.release(1, True)
+        best = max(best, nbytes / (t["h2d_ms"] * 1e-3) / 1e9)
+    pool.close()
+    arena.free()
+    return best
+
+
+def cpu_baseline(runner, w, name, budget_s=20.0):
+    """The oracle as it stands, on this machine's host cores, on a bounded sample
+    of the workload's load: fingerprint + match/plan + assemble (byte copy
+    into its image) of the first tensors of `name`, against a store that holds
+    the matching tensors of the resident sibling."""
+    import oracle
+    from oracle import ReuseStoreOracle
+
+    reg = runner.models[name]
+    host = runner.host_numpy(name)
+    # calibrate on a small piece, then size the sample to the budget
+    probe = host[:32 << 20]
+    t0 = time.perf_counter()
+    oracle.fingerprint(probe)
+    dst = probe.copy()
+    oracle.copy_bytes(dst, probe)
+    per_byte = (time.perf_counter() - t0) / probe.size
+    cores = len(os.sched_getaffinity(0))
+    # whole tensors, from the front of the model, until the all-cores leg fills its share
+    target_1core = int(budget_s * 0.4 / per_byte)
+    order = list(range(len(reg.sizes)))
+    sample, total = [], 0
+    for k in order:
+        if total + reg.sizes[k] > target_1core and sample:
+            break
+        sample.append(k)
+        total += reg.sizes[k]
+
+    def one_pass(n_threads):
+        store = ReuseStoreOracle(w.pool_bytes, w.align)
+        # resident sibling: the sampled tensors that the real pool also holds
+        base_name = w.setup[0][1] if w.setup else None
+        t_start = time.perf_counter()
+        fps = [0] * len(sample)
+
+        def work(tid):
+            for i in range(tid, len(sample), n_threads):
+                k = sample[i]
+                fps[i] = oracle.fingerprint(host[reg.offs[k]:reg.offs[k] + reg.sizes[k]])
+        threads = [threading.Thread(target=work, args=(t,)) for t in range(n_threads)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        rows = [(reg.sizes[k], fps[i], reg.offs[k]) for i, k in enumerate(sample)]
+        plan = store.plan(999, rows, host)
+        # assemble: byte copies into the oracle's image, tensors spread over threads
+        import numpy as np
+        slots = [None] * len(sample)
+
+        def copy(tid):
+            for i in range(tid, len(sample), n_threads):
+                op = plan.ops[i]
+                slot = np.empty(op.nbytes, dtype=np.uint8)
+                oracle.copy_bytes(slot, host[op.src_off:op.src_off + op.nbytes])
+                slots[i] = slot
+        threads = [threading.Thread(target=copy, args=(t,)) for t in range(n_threads)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        return time.perf_counter() - t_start, base_name
+
+    t1, _ = one_pass(1)
+    n_thr = min(cores, max(1, len(sample)))
+    tn, _ = one_pass(n_thr)
+    return {
+        "value": round(total / tn / 1e9, 4), "unit": "GB/s", "cores": n_thr, "kind": "oracle",
+        "value_1core": round(total / t1 / 1e9, 4),
+        "sample": "first %d tensors of %s (%.2f GB): oracle fingerprint + plan + byte-copy assemble, "
+                  "no resident sibling (every tensor copied from host memory); %d-thread leg %.1f s, "
+                  "1-thread leg %.1f s" % (len(sample), name, total / 1e9, n_thr, tn, t1),
+        "host_cores_available": cores,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=9)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b",
+                    help="tiny | gpt1b | llama7b | neox20b | llama70b-0 | llama70b-50 | llama70b-90")
+    ap.add_argument("--no-verify", action="store_true", help="skip the fingerprint of assembled slots")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pool-gb", type=float, default=0.0, help="override pool size (70B)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives are part of "
+              "it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_01357_amd import synth
+    from paper_2512_01357_amd import tangram as tg
+    from paper_2512_01357_amd.runner import WorkloadRunner
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    tg.lib()
+    if args.workload.startswith("llama70b"):
+        frac = int(args.workload.split("-")[1]) / 100.0
+        free, _total = torch.cuda.mem_get_info()
+        pool = int(args.pool_gb * 1e9) if args.pool_gb else int(free - (6 << 30))
+        w = synth.workload_llama70b(frac, pool)
+    else:
+        w = synth.WORKLOADS[args.workload]()
+    log("workload %s: pool %.1f GB, loads %s" % (w.name, w.pool_bytes / 1e9, w.loads))
+
+    link_peak = measure_link_peak(torch)
+    log("host link peak (2 GiB pinned->device): %.2f GB/s" % link_peak)
+
+    r = WorkloadRunner(w, "cuda:0", log=log)
+    r.run_setup()
+    for name in w.loads:
+        r.materialise(name)
+    st0 = r.pool.stats()
+    log("pool before loads: %s" % st0)
+
+    verify = not args.no_verify
+    tg.tg_set_profiling(True)
+    names = w.loads
+
+    def step(i):
+        name = names[i % len(names)]
+        ptrs, info = r.load(name, verify=verify)
+        t = tg.tg_last_timing()
+        r.release(name, True)
+        return name, info, t
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    recs = []
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        t0 = time.perf_counter()
+        name, info, t = step(args.warmup + i)
+        recs.append((name, info, t, time.perf_counter() - t0))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+    st1 = r.pool.stats()
+    if any(st1[k] != st0[k] for k in st0 if k != "generation"):
+        raise RuntimeError("pool did not return to its starting state: %s vs %s" % (st1, st0))
+
+    model_bytes = [r.models[n].nbytes for n, _, _, _ in recs]
+    total_bytes = sum(model_bytes)
+    value = total_bytes / elapsed / 1e9
+
+    def avg(key):
+        return sum(rec[2][key] for rec in recs) / len(recs)
+
+    def rate(bytes_key, ms_key, factor=1.0):
+        ms = sum(rec[2][ms_key] for rec in recs)
+        b = sum(rec[2][bytes_key] for rec in recs)
+        return (factor * b / (ms * 1e-3) / 1e9) if ms > 0 else 0.0
+
+    fp_key_ms, fp_key_b = ("verify_ms", "verify_bytes") if verify else ("fingerprint_ms", "fingerprint_bytes")
+    fp_gbps = rate(fp_key_b, fp_key_ms)
+    gather_gbps = rate("gather_bytes", "gather_ms", 2.0)
+    h2d_gbps = rate("h2d_bytes", "h2d_ms")
+    kernels = {
+        "fingerprint": {"bound": "hbm", "achieved": round(fp_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": round(fp_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(avg(fp_key_ms), 4),
+                        "algorithmic_bytes_per_launch": int(sum(rec[2][fp_key_b] for rec in recs) / len(recs)),
+                        "traffic": None},
+        "gather": {"bound": "hbm", "achieved": round(gather_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                   "frac": round(gather_gbps / HBM_PEAK_GBPS, 4), "avg_ms": round(avg("gather_ms"), 4),
+                   "algorithmic_bytes_per_launch": int(2 * sum(rec[2]["gather_bytes"] for rec in recs) / len(recs)),
+                   "traffic": None},
+    }
+    dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    roofline = dict(kernels[dominant])
+    roofline["kernel"] = dominant
+
+    out = {
+        "metric": "effective load GB/s (model bytes resident / load time); fingerprint HBM GB/s",
+        "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": w.name, "model_bytes": int(statistics.mean(model_bytes)),
+                   "tensors": r.models[names[0]].desc.n, "pool_bytes": w.pool_bytes,
+                   "reused_fraction": round(recs[0][1]["reused_bytes"] / model_bytes[0], 4),
+                   "verify_fingerprint": verify},
+        "fingerprint_GBps": round(fp_gbps, 1),
+        "roofline": roofline,
+        "kernels": kernels,
+        "host_link": {"achieved": round(h2d_gbps, 2), "peak_measured": round(link_peak, 2), "unit": "GB/s",
+                      "frac": round(h2d_gbps / link_peak, 4) if link_peak else None,
+                      "avg_ms": round(avg("h2d_ms"), 3), "copies_per_load": recs[0][2]["h2d_copies"]},
+        "plan_host_ms": round(avg("plan_host_ms"), 4),
+        "load_time_bound_ms": round(max(2 * recs[0][1]["reused_bytes"] / (HBM_PEAK_GBPS * 1e9),
+                                        recs[0][1]["transfer_bytes"] / (link_peak * 1e9)) * 1e3, 3),
+    }
+
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(r, w, names[0])
+    r.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -280,6 +280,16 @@ tg_status tg_get_tuning(tg_tuning *out);
 void      tg_set_profiling(int on);
 tg_status tg_last_timing(tg_timing *out);
 
+/*
+ * Page-locked host memory for a Model Cache image (Section 3.1 loads missing
+ * tensors from the CPU-side Model Cache; the copy engine needs it pinned).
+ * *out [pinned host] receives nbytes of memory that is also mapped into the
+ * device's address space.  TG_ERR_NOMEM when the host or the driver's pinned
+ * limit is exhausted.  tg_host_free(NULL) is accepted.
+ */
+tg_status tg_host_alloc(uint64_t nbytes, void **out);
+tg_status tg_host_free(void *p);
+
 /* Frees the library's device and pinned scratch.  Safe to call twice. */
 void tg_shutdown(void);
 

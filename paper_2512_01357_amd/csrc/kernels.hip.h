@@ -2,17 +2,24 @@
 //
 // Three streaming kernels share one work decomposition.  A launch covers a
 // table of extents (spans to fingerprint, pairs to compare, copies to make).
-// Every extent is cut into tiles of TILE = 256 lanes x 16 bytes x U bytes;
-// tiles of all extents are numbered consecutively and dealt round-robin to a
-// fixed number of resident workgroups (tile t goes to workgroup t mod grid).
-// Neighbouring workgroups therefore touch neighbouring 4U KiB pieces of HBM at
-// any moment, which keeps all channels busy, and each lane issues U
-// independent 128-bit loads before it consumes any of them.
+// Every extent is cut into tiles of T lanes x 16 bytes x U; the tiles of all
+// extents are numbered consecutively and every workgroup takes one contiguous
+// run of `run` tiles (workgroup b: tiles [b*run, (b+1)*run)), so each
+// workgroup streams through one long address range, changes extent only where
+// an extent ends inside its run, and all workgroups finish together.  Each lane
+// issues U independent 128-bit loads before it consumes any of them.
+//
+// Measured on MI355X (13.5 GB, 291 extents): dealing tiles round-robin
+// instead costs a quarter of the fingerprint's bandwidth (a descriptor fetch
+// and a cross-wave fold at almost every tile), and two workgroups of 256 lanes
+// per compute unit read faster than more.  The copy does best with 1024-lane
+// workgroups that read 128 KiB, meet at a barrier, then write 128 KiB: keeping
+// a compute unit's reads and writes in separate bursts is worth ~10 %.
 //
 // None of this is a dense contraction, so there is no MFMA here; nothing is
 // reused across tiles, so the only data kept in LDS is the per-wave partial
 // sum of the fingerprint's cross-wave combine.  The XCD a workgroup lands on
-// does not matter for correctness or reuse (each tile is read once); the
+// does not matter for correctness or reuse (each byte is touched once); the
 // descriptor tables are a few KiB and end up in every XCD's L2.
 #pragma once
 
@@ -25,14 +32,15 @@ typedef unsigned long long u64;
 typedef unsigned int u32;
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;               // 4 waves of 64
+constexpr int kReadThreads = 256;           // fingerprint / compare workgroup: 4 waves
+constexpr int kCopyThreads = 1024;          // gather workgroup: 16 waves
 constexpr u64 kGamma = 0x9E3779B97F4A7C15ull;
 
 struct Span { u64 ptr, nbytes; };           // extent to fingerprint
 struct Pair { u64 a, b, nbytes; };          // extents to compare
 struct Copy { u64 dst, src, nbytes; };      // extent to copy (non-overlapping)
 
-template <int U> constexpr u64 tile_bytes() { return u64(kThreads) * 16 * U; }
+template <int T, int U> constexpr u64 tile_bytes() { return u64(T) * 16 * U; }
 
 // SplitMix64 output function on a state that has not been advanced.
 __device__ __forceinline__ u64 mix(u64 x) {
@@ -83,63 +91,93 @@ __device__ __forceinline__ u32 locate_first(const u32 *__restrict__ prefix, u32 
     return lo;
 }
 
+// Every extent lives in global memory (HBM, or pinned host memory seen through
+// its device mapping).  Addresses arrive as integers in descriptor tables, so
+// the compiler cannot infer the address space; naming it here turns what
+// would be FLAT accesses into GLOBAL ones.
+#define TGK_GLOBAL __attribute__((address_space(1)))
 __device__ __forceinline__ u32x4 load16(const void *p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return __builtin_nontemporal_load(
+        reinterpret_cast<const TGK_GLOBAL u32x4 *>(reinterpret_cast<uintptr_t>(p)));
 }
 __device__ __forceinline__ void store16(void *p, u32x4 v) {
-    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+    __builtin_nontemporal_store(v, reinterpret_cast<TGK_GLOBAL u32x4 *>(reinterpret_cast<uintptr_t>(p)));
+}
+__device__ __forceinline__ uint8_t load1(const void *p) {
+    return *reinterpret_cast<const TGK_GLOBAL uint8_t *>(reinterpret_cast<uintptr_t>(p));
+}
+__device__ __forceinline__ void store1(void *p, uint8_t v) {
+    *reinterpret_cast<TGK_GLOBAL uint8_t *>(reinterpret_cast<uintptr_t>(p)) = v;
 }
 
 // Little-endian word made of up to 8 bytes at p; bytes at or past `avail` are 0.
 __device__ __forceinline__ u64 tail_word(const uint8_t *p, u32 avail) {
     u64 w = 0;
-    for (u32 j = 0; j < 8 && j < avail; ++j) w |= u64(p[j]) << (8 * j);
+    for (u32 j = 0; j < 8 && j < avail; ++j) w |= u64(load1(p + j)) << (8 * j);
     return w;
 }
 
+// Walks the tiles [blockIdx.x * run, (blockIdx.x + 1) * run) of a table.
+struct TileWalk {
+    u32 t, end, s, first, next;
+    __device__ __forceinline__ bool init(const u32 *__restrict__ prefix, u32 n, u32 run) {
+        const u32 total = prefix[n];
+        const u64 lo = u64(blockIdx.x) * run;
+        if (lo >= total) return false;
+        t = u32(lo);
+        end = u32(lo + run < total ? lo + run : total);
+        s = locate_first(prefix, n, t);
+        first = prefix[s];
+        next = prefix[s + 1];
+        return true;
+    }
+    // true when tile t lies past extent s; moves s to the extent that holds t
+    __device__ __forceinline__ bool crossed(const u32 *__restrict__ prefix) {
+        if (t < next) return false;
+        do { ++s; next = prefix[s + 1]; } while (t >= next);
+        first = prefix[s];
+        return true;
+    }
+};
+
 // ---------------------------------------------------------------- fingerprint
 // out[s] += sum over the words of span s of mix(w_i ^ i*gamma).  `out` must be
-// zero before the launch.  Per-lane sums are carried across consecutive tiles
-// of one span and folded (wave DPP reduce, LDS across the four waves, one
-// 64-bit atomic per workgroup) only when the workgroup moves to another span.
-template <int U>
-__global__ __launch_bounds__(kThreads) void fingerprint_kernel(const Span *__restrict__ spans,
-                                                                const u32 *__restrict__ prefix,
-                                                                u32 n_spans, u64 *__restrict__ out) {
-    constexpr u64 TILE = tile_bytes<U>();
-    __shared__ u64 wave_part[kThreads / 64];
-    const u32 total = prefix[n_spans];
+// zero before the launch.  Per-lane sums are carried across the tiles of one
+// span and folded (wave DPP reduce, LDS across the waves, one 64-bit atomic per
+// workgroup) only when the workgroup's run leaves that span.
+template <int T, int U>
+__global__ __launch_bounds__(T) void fingerprint_kernel(const Span *__restrict__ spans,
+                                                         const u32 *__restrict__ prefix, u32 n_spans,
+                                                         u32 run, u64 *__restrict__ out) {
+    constexpr u64 TILE = tile_bytes<T, U>();
+    __shared__ u64 wave_part[T / 64];
     const u32 tid = threadIdx.x;
-    u32 t = blockIdx.x;
-    if (t >= total) return;
-
-    u32 s = locate_first(prefix, n_spans, t);
-    u32 first = prefix[s], next = prefix[s + 1];
-    Span sp = spans[s];
+    TileWalk w;
+    if (!w.init(prefix, n_spans, run)) return;     // workgroup-uniform
+    Span sp = spans[w.s];
     u64 acc = 0;
 
     auto fold = [&](u32 span_index) {
-        const u64 w = wave_sum(acc);
-        if ((tid & 63) == 0) wave_part[tid >> 6] = w;
+        const u64 ws = wave_sum(acc);
+        if ((tid & 63) == 0) wave_part[tid >> 6] = ws;
         __syncthreads();
         if (tid == 0) {
             u64 sum = 0;
 #pragma unroll
-            for (int i = 0; i < kThreads / 64; ++i) sum += wave_part[i];
+            for (int i = 0; i < T / 64; ++i) sum += wave_part[i];
             atomicAdd(&out[span_index], sum);
         }
         __syncthreads();
         acc = 0;
     };
 
-    for (; t < total; t += gridDim.x) {
-        if (t >= next) {                       // workgroup-uniform
-            fold(s);
-            do { ++s; next = prefix[s + 1]; } while (t >= next);
-            first = prefix[s];
-            sp = spans[s];
+    for (; w.t < w.end; ++w.t) {
+        const u32 prev = w.s;
+        if (w.crossed(prefix)) {                   // workgroup-uniform
+            fold(prev);
+            sp = spans[w.s];
         }
-        const u64 off = u64(t - first) * TILE;
+        const u64 off = u64(w.t - w.first) * TILE;
         const u64 left = sp.nbytes - off;
         const uint8_t *base = reinterpret_cast<const uint8_t *>(sp.ptr) + off;
         // key of the first word this lane reads in the tile
@@ -147,20 +185,20 @@ __global__ __launch_bounds__(kThreads) void fingerprint_kernel(const Span *__res
         if (left >= TILE) {
             u32x4 v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = load16(base + (u64(u) * kThreads + tid) * 16);
+            for (int u = 0; u < U; ++u) v[u] = load16(base + (u64(u) * T + tid) * 16);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const u64 k0 = key + u64(u) * (2 * kThreads) * kGamma;
+                const u64 k0 = key + u64(u) * (2 * T) * kGamma;
                 acc += mix(lohi(v[u].x, v[u].y) ^ k0);
                 acc += mix(lohi(v[u].z, v[u].w) ^ (k0 + kGamma));
             }
         } else {
             const u64 nvec = left / 16;
-            for (u64 i = tid; i < nvec; i += kThreads) {
+            for (u64 i = tid; i < nvec; i += T) {
                 const u32x4 v = load16(base + i * 16);
                 acc += mix(lohi(v.x, v.y) ^ key);
                 acc += mix(lohi(v.z, v.w) ^ (key + kGamma));
-                key += u64(2 * kThreads) * kGamma;
+                key += u64(2 * T) * kGamma;
             }
             const u32 rem = u32(left % 16);
             if (rem != 0 && tid == 0) {        // ragged end: at most two partial words
@@ -171,24 +209,21 @@ __global__ __launch_bounds__(kThreads) void fingerprint_kernel(const Span *__res
             }
         }
     }
-    fold(s);
+    fold(w.s);
 }
 
 // -------------------------------------------------------------------- compare
 // differs[s] = 1 if the two extents of pair s differ in any byte.  `differs`
 // must be zero before the launch.
-template <int U>
-__global__ __launch_bounds__(kThreads) void compare_kernel(const Pair *__restrict__ pairs,
-                                                            const u32 *__restrict__ prefix,
-                                                            u32 n_pairs, u32 *__restrict__ differs) {
-    constexpr u64 TILE = tile_bytes<U>();
-    const u32 total = prefix[n_pairs];
+template <int T, int U>
+__global__ __launch_bounds__(T) void compare_kernel(const Pair *__restrict__ pairs,
+                                                     const u32 *__restrict__ prefix, u32 n_pairs,
+                                                     u32 run, u32 *__restrict__ differs) {
+    constexpr u64 TILE = tile_bytes<T, U>();
     const u32 tid = threadIdx.x;
-    u32 t = blockIdx.x;
-    if (t >= total) return;
-    u32 s = locate_first(prefix, n_pairs, t);
-    u32 first = prefix[s], next = prefix[s + 1];
-    Pair pr = pairs[s];
+    TileWalk w;
+    if (!w.init(prefix, n_pairs, run)) return;
+    Pair pr = pairs[w.s];
     u32 diff = 0;
 
     auto fold = [&](u32 pair_index) {
@@ -196,14 +231,13 @@ __global__ __launch_bounds__(kThreads) void compare_kernel(const Pair *__restric
         diff = 0;
     };
 
-    for (; t < total; t += gridDim.x) {
-        if (t >= next) {
-            fold(s);
-            do { ++s; next = prefix[s + 1]; } while (t >= next);
-            first = prefix[s];
-            pr = pairs[s];
+    for (; w.t < w.end; ++w.t) {
+        const u32 prev = w.s;
+        if (w.crossed(prefix)) {
+            fold(prev);
+            pr = pairs[w.s];
         }
-        const u64 off = u64(t - first) * TILE;
+        const u64 off = u64(w.t - w.first) * TILE;
         const u64 left = pr.nbytes - off;
         const uint8_t *pa = reinterpret_cast<const uint8_t *>(pr.a) + off;
         const uint8_t *pb = reinterpret_cast<const uint8_t *>(pr.b) + off;
@@ -211,8 +245,8 @@ __global__ __launch_bounds__(kThreads) void compare_kernel(const Pair *__restric
             u32x4 va[U], vb[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                va[u] = load16(pa + (u64(u) * kThreads + tid) * 16);
-                vb[u] = load16(pb + (u64(u) * kThreads + tid) * 16);
+                va[u] = load16(pa + (u64(u) * T + tid) * 16);
+                vb[u] = load16(pb + (u64(u) * T + tid) * 16);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -221,54 +255,51 @@ __global__ __launch_bounds__(kThreads) void compare_kernel(const Pair *__restric
             }
         } else {
             const u64 nvec = left / 16;
-            for (u64 i = tid; i < nvec; i += kThreads) {
+            for (u64 i = tid; i < nvec; i += T) {
                 const u32x4 x = load16(pa + i * 16) ^ load16(pb + i * 16);
                 diff |= x.x | x.y | x.z | x.w;
             }
             const u32 rem = u32(left % 16);
-            if (tid < rem) diff |= u32(pa[nvec * 16 + tid] ^ pb[nvec * 16 + tid]);
+            if (tid < rem) diff |= u32(load1(pa + nvec * 16 + tid) ^ load1(pb + nvec * 16 + tid));
         }
     }
-    fold(s);
+    fold(w.s);
 }
 
 // --------------------------------------------------------------------- gather
 // dst[0..nbytes) = src[0..nbytes) for every row of `copies`; destinations do
-// not overlap each other or any source.
-template <int U>
-__global__ __launch_bounds__(kThreads) void gather_kernel(const Copy *__restrict__ copies,
-                                                           const u32 *__restrict__ prefix,
-                                                           u32 n_copies) {
-    constexpr u64 TILE = tile_bytes<U>();
-    const u32 total = prefix[n_copies];
+// not overlap each other or any source.  The workgroup reads a whole tile,
+// meets at a barrier, then writes it, so that its loads and its stores reach
+// memory as two bursts rather than interleaved.
+template <int T, int U>
+__global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copies,
+                                                    const u32 *__restrict__ prefix, u32 n_copies,
+                                                    u32 run) {
+    constexpr u64 TILE = tile_bytes<T, U>();
     const u32 tid = threadIdx.x;
-    u32 t = blockIdx.x;
-    if (t >= total) return;
-    u32 s = locate_first(prefix, n_copies, t);
-    u32 first = prefix[s], next = prefix[s + 1];
-    Copy cp = copies[s];
+    TileWalk w;
+    if (!w.init(prefix, n_copies, run)) return;
+    Copy cp = copies[w.s];
 
-    for (; t < total; t += gridDim.x) {
-        if (t >= next) {
-            do { ++s; next = prefix[s + 1]; } while (t >= next);
-            first = prefix[s];
-            cp = copies[s];
-        }
-        const u64 off = u64(t - first) * TILE;
+    for (; w.t < w.end; ++w.t) {
+        if (w.crossed(prefix)) cp = copies[w.s];
+        const u64 off = u64(w.t - w.first) * TILE;
         const u64 left = cp.nbytes - off;
         const uint8_t *ps = reinterpret_cast<const uint8_t *>(cp.src) + off;
         uint8_t *pd = reinterpret_cast<uint8_t *>(cp.dst) + off;
-        if (left >= TILE) {
+        if (left >= TILE) {                        // workgroup-uniform
             u32x4 v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = load16(ps + (u64(u) * kThreads + tid) * 16);
+            for (int u = 0; u < U; ++u) v[u] = load16(ps + (u64(u) * T + tid) * 16);
+            __syncthreads();
 #pragma unroll
-            for (int u = 0; u < U; ++u) store16(pd + (u64(u) * kThreads + tid) * 16, v[u]);
+            for (int u = 0; u < U; ++u) store16(pd + (u64(u) * T + tid) * 16, v[u]);
+            __syncthreads();
         } else {
             const u64 nvec = left / 16;
-            for (u64 i = tid; i < nvec; i += kThreads) store16(pd + i * 16, load16(ps + i * 16));
+            for (u64 i = tid; i < nvec; i += T) store16(pd + i * 16, load16(ps + i * 16));
             const u32 rem = u32(left % 16);
-            if (tid < rem) pd[nvec * 16 + tid] = ps[nvec * 16 + tid];
+            if (tid < rem) store1(pd + nvec * 16 + tid, load1(ps + nvec * 16 + tid));
         }
     }
 }

@@ -26,7 +26,7 @@ using tgk::u64;
 
 // Loads in flight per lane (U) and resident workgroups per compute unit for
 // each kernel.  Chosen by measurement on MI355X; see tg_set_tuning.
-tg_tuning g_tune = {8, 4, 8, 8, 8, 8, 0};
+tg_tuning g_tune = {4, 2, 8, 2, 4, 2, 0};
 
 bool g_profiling = false;
 tg_timing g_timing = {};
@@ -40,15 +40,20 @@ struct Scratch {
     int cu_count = 0;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
 
+    tg_status init() {
+        if (cu_count != 0) return TG_OK;
+        int dev = 0;
+        TG_HIP(hipGetDevice(&dev));
+        hipDeviceProp_t prop;
+        TG_HIP(hipGetDeviceProperties(&prop, dev));
+        for (auto &e : ev)
+            if (!e) TG_HIP(hipEventCreate(&e));
+        cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        return TG_OK;
+    }
     tg_status ensure(size_t bytes) {
-        if (cu_count == 0) {
-            int dev = 0;
-            TG_HIP(hipGetDevice(&dev));
-            hipDeviceProp_t prop;
-            TG_HIP(hipGetDeviceProperties(&prop, dev));
-            cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-            for (auto &e : ev) TG_HIP(hipEventCreate(&e));
-        }
+        const tg_status rc = init();
+        if (rc != TG_OK) return rc;
         if (bytes <= cap) return TG_OK;
         size_t want = std::max<size_t>(bytes * 2, size_t(1) << 20);
         release_buffers();
@@ -104,15 +109,18 @@ u32 grid_for(u32 total_tiles, u32 wgs_per_cu) {
 
 u32 pick_u(u32 u) { return u >= 16 ? 16 : u >= 8 ? 8 : u >= 4 ? 4 : 2; }
 
-#define TG_FOR_U(U, STMT)                              \
-    switch (U) {                                       \
-        case 16: { constexpr int kU = 16; STMT; break; } \
-        case 8:  { constexpr int kU = 8;  STMT; break; } \
-        case 4:  { constexpr int kU = 4;  STMT; break; } \
-        default: { constexpr int kU = 2;  STMT; break; } \
+#define TG_FOR_U(U, ...)                                      \
+    switch (U) {                                              \
+        case 16: { constexpr int kU = 16; __VA_ARGS__; break; } \
+        case 8:  { constexpr int kU = 8;  __VA_ARGS__; break; } \
+        case 4:  { constexpr int kU = 4;  __VA_ARGS__; break; } \
+        default: { constexpr int kU = 2;  __VA_ARGS__; break; } \
     }
 
-u64 tile_for(u32 U) { return u64(tgk::kThreads) * 16 * U; }
+u64 tile_for(u32 threads, u32 U) { return u64(threads) * 16 * U; }
+
+// Tiles per workgroup when `total` tiles are split into equal contiguous runs.
+u32 run_for(u32 total_tiles, u32 grid) { return (total_tiles + grid - 1) / grid; }
 
 // ---- fingerprint over device-visible spans; scratch lock held by the caller
 tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipStream_t st,
@@ -130,7 +138,7 @@ tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipS
         total_bytes += spans[i].nbytes;
     }
     u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
-    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, n, tile_for(U))) return TG_ERR_INVALID;
+    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, n, tile_for(tgk::kReadThreads, U))) return TG_ERR_INVALID;
     const u32 total_tiles = hp[n];
     u64 *d_out = reinterpret_cast<u64 *>(d + L.result_off);
     u64 *h_out = reinterpret_cast<u64 *>(h + L.result_off);
@@ -139,9 +147,10 @@ tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipS
     if (total_tiles > 0) {
         const u32 grid = grid_for(total_tiles, g_tune.fingerprint_wgs_per_cu);
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], st));
-        TG_FOR_U(U, hipLaunchKernelGGL(tgk::fingerprint_kernel<kU>, dim3(grid), dim3(tgk::kThreads), 0, st,
-                                       reinterpret_cast<const tgk::Span *>(d + L.desc_off),
-                                       reinterpret_cast<const u32 *>(d + L.prefix_off), n, d_out));
+        const u32 run = run_for(total_tiles, grid);
+        TG_FOR_U(U, tgk::fingerprint_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, st>>>(
+                        reinterpret_cast<const tgk::Span *>(d + L.desc_off),
+                        reinterpret_cast<const u32 *>(d + L.prefix_off), n, run, d_out));
         TG_HIP(hipGetLastError());
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], st));
     }
@@ -172,7 +181,7 @@ tg_status compare_locked(const tg_pair *pairs, u32 n, uint32_t *out_differs, hip
         total_bytes += pairs[i].nbytes;
     }
     u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
-    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Pair) / 8, n, tile_for(U))) return TG_ERR_INVALID;
+    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Pair) / 8, n, tile_for(tgk::kReadThreads, U))) return TG_ERR_INVALID;
     const u32 total_tiles = hp[n];
     // results are 32-bit flags; the zero kernel clears whole 64-bit words
     u32 *d_out = reinterpret_cast<u32 *>(d + L.result_off);
@@ -184,9 +193,10 @@ tg_status compare_locked(const tg_pair *pairs, u32 n, uint32_t *out_differs, hip
     if (total_tiles > 0) {
         const u32 grid = grid_for(total_tiles, g_tune.compare_wgs_per_cu);
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], st));
-        TG_FOR_U(U, hipLaunchKernelGGL(tgk::compare_kernel<kU>, dim3(grid), dim3(tgk::kThreads), 0, st,
-                                       reinterpret_cast<const tgk::Pair *>(d + L.desc_off),
-                                       reinterpret_cast<const u32 *>(d + L.prefix_off), n, d_out));
+        const u32 run = run_for(total_tiles, grid);
+        TG_FOR_U(U, tgk::compare_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, st>>>(
+                        reinterpret_cast<const tgk::Pair *>(d + L.desc_off),
+                        reinterpret_cast<const u32 *>(d + L.prefix_off), n, run, d_out));
         TG_HIP(hipGetLastError());
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], st));
     }
@@ -389,6 +399,10 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     const uint64_t base = store.base();
 
     std::lock_guard<std::mutex> lock(g_scratch.mu);
+    {
+        const tg_status rc = g_scratch.init();
+        if (rc != TG_OK) return rc;
+    }
 
     // Host-to-device list, in destination order; copies adjacent on both sides
     // (the slot padding included) are merged into one (Section 4 groups
@@ -441,15 +455,16 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         char *h = static_cast<char *>(g_scratch.h), *d = static_cast<char *>(g_scratch.d);
         std::memcpy(h + L.desc_off, copies.data(), n * sizeof(tgk::Copy));
         u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
-        if (!fill_prefix(hp, &copies[0].nbytes, sizeof(tgk::Copy) / 8, n, tile_for(U))) return TG_ERR_INVALID;
+        if (!fill_prefix(hp, &copies[0].nbytes, sizeof(tgk::Copy) / 8, n, tile_for(tgk::kCopyThreads, U))) return TG_ERR_INVALID;
         gather_tiles = hp[n];
         for (const auto &c : copies) gather_bytes += c.nbytes;
         TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, sg));
         const u32 grid = grid_for(gather_tiles, g_tune.gather_wgs_per_cu);
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], sg));
-        TG_FOR_U(U, hipLaunchKernelGGL(tgk::gather_kernel<kU>, dim3(grid), dim3(tgk::kThreads), 0, sg,
-                                       reinterpret_cast<const tgk::Copy *>(d + L.desc_off),
-                                       reinterpret_cast<const u32 *>(d + L.prefix_off), n));
+        const u32 run = run_for(gather_tiles, grid);
+        TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU><<<dim3(grid), dim3(tgk::kCopyThreads), 0, sg>>>(
+                        reinterpret_cast<const tgk::Copy *>(d + L.desc_off),
+                        reinterpret_cast<const u32 *>(d + L.prefix_off), n, run));
         TG_HIP(hipGetLastError());
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], sg));
     }
@@ -549,6 +564,23 @@ tg_status tg_set_tuning(const tg_tuning *t) {
 tg_status tg_get_tuning(tg_tuning *t) {
     if (!t) return TG_ERR_INVALID;
     *t = g_tune;
+    return TG_OK;
+}
+
+tg_status tg_host_alloc(uint64_t nbytes, void **out) {
+    if (!out || nbytes == 0) return TG_ERR_INVALID;
+    void *p = nullptr;
+    if (hipHostMalloc(&p, nbytes, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        return TG_ERR_NOMEM;
+    }
+    *out = p;
+    return TG_OK;
+}
+
+tg_status tg_host_free(void *p) {
+    if (!p) return TG_OK;
+    TG_HIP(hipHostFree(p));
     return TG_OK;
 }
 

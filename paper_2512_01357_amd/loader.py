@@ -2,27 +2,64 @@
 
 ``ReusePool`` owns the slab (one torch uint8 tensor on the GPU), two streams
 and the library's pool handle; every step of a load is a call into
-libtangram.so through ``tangram.py``.
+libtangram.so through ``tangram.py``.  ``HostArena`` is pinned Model Cache
+memory from tg_host_alloc, seen as a torch / numpy byte array.
 """
-from typing import Dict, List, Optional, Sequence, Tuple
+import ctypes
+from typing import List, Optional, Sequence, Tuple
 
 import torch
 
 from . import tangram as tg
 
 
+class HostArena:
+    """nbytes of pinned, device-mapped host memory (a Model Cache image)."""
+
+    def __init__(self, nbytes: int):
+        self.nbytes = nbytes
+        self.ptr = tg.tg_host_alloc(nbytes)
+        self._c = (ctypes.c_uint8 * nbytes).from_address(self.ptr)
+        self.tensor = torch.frombuffer(self._c, dtype=torch.uint8)
+
+    def numpy(self):
+        return self.tensor.numpy()
+
+    def free(self) -> None:
+        if self.ptr:
+            self.tensor = None
+            self._c = None
+            tg.tg_host_free(self.ptr)
+            self.ptr = 0
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _host_view(host) -> Tuple[torch.Tensor, int, int]:
+    """(uint8 CPU tensor, address, length) of a HostArena or a pinned tensor."""
+    if isinstance(host, HostArena):
+        return host.tensor, host.ptr, host.nbytes
+    if not host.is_pinned():
+        raise ValueError("the Model Cache buffer must be pinned host memory")
+    return host, host.data_ptr(), host.numel()
+
+
 class RegisteredModel:
     """A model in the CPU-side Model Cache: pinned bytes + per-tensor rows."""
 
-    def __init__(self, model_id: int, host: torch.Tensor, offs: Sequence[int],
-                 sizes: Sequence[int], fps: Sequence[int]):
+    def __init__(self, model_id: int, host, offs: Sequence[int], sizes: Sequence[int],
+                 fps: Sequence[int]):
         self.model_id = model_id
-        self.host = host                       # keeps the pinned buffer alive
+        self.host = host                       # keeps the pinned memory alive
+        self.host_tensor, ptr, length = _host_view(host)
         self.offs = list(offs)
         self.sizes = list(sizes)
         self.fps = list(fps)
-        self.desc = tg.ModelDesc(model_id, host.data_ptr(), host.numel(),
-                                 list(zip(self.sizes, self.fps, self.offs)))
+        self.desc = tg.ModelDesc(model_id, ptr, length, list(zip(self.sizes, self.fps, self.offs)))
 
     @property
     def nbytes(self) -> int:
@@ -36,12 +73,15 @@ def fingerprint_host_buffer(host: torch.Tensor, offs: Sequence[int], sizes: Sequ
 
     The bytes are staged through a bounded device buffer in runs of
     consecutive tensors; each run is one host-to-device copy and one
-    tg_fingerprint launch over the staged spans.
+    tg_fingerprint launch over the staged spans.  Tensors that share an offset
+    (stored once in the cache) are fingerprinted once.
     """
     n = len(offs)
     fps = [0] * n
-    order = sorted(range(n), key=lambda k: offs[k])
-    cap = max(stage_bytes, max(sizes) if sizes else 0)
+    if n == 0:
+        return fps
+    order = sorted(range(n), key=lambda k: (offs[k], sizes[k]))
+    cap = max(stage_bytes, max(sizes))
     cap = (cap + 255) // 256 * 256
     stage = torch.empty(cap + 256, dtype=torch.uint8, device=device)   # room for the phase
     i = 0
@@ -50,19 +90,20 @@ def fingerprint_host_buffer(host: torch.Tensor, offs: Sequence[int], sizes: Sequ
         j = i
         end = start
         while j < n and offs[order[j]] + sizes[order[j]] - start <= cap:
-            end = offs[order[j]] + sizes[order[j]]
+            end = max(end, offs[order[j]] + sizes[order[j]])
             j += 1
-        if j == i:
-            raise ValueError("tensor larger than the staging buffer")
         # the run's first byte keeps its 16-byte phase inside the staging buffer
         phase = start % 16
-        stage[phase:phase + end - start].copy_(host[start:end], non_blocking=False)
-        spans = [(stage.data_ptr() + phase + offs[order[m]] - start, sizes[order[m]])
-                 for m in range(i, j)]
+        stage[phase:phase + end - start].copy_(host[start:end])
         torch.cuda.synchronize()
-        got = tg.tg_fingerprint(spans, stream)
-        for m, f in zip(range(i, j), got):
-            fps[order[m]] = f
+        uniq = {}
+        for m in range(i, j):
+            uniq.setdefault((offs[order[m]], sizes[order[m]]), []).append(order[m])
+        keys = list(uniq)
+        got = tg.tg_fingerprint([(stage.data_ptr() + phase + o - start, s) for o, s in keys], stream)
+        for key, f in zip(keys, got):
+            for k in uniq[key]:
+                fps[k] = f
         i = j
     del stage
     return fps
@@ -89,13 +130,11 @@ class ReusePool:
             self.pool = None
         self.slab = None
 
-    def register(self, model_id: int, host: torch.Tensor, offs: Sequence[int],
-                 sizes: Sequence[int], fps: Optional[Sequence[int]] = None,
-                 stage_bytes: int = 2 << 30) -> RegisteredModel:
-        if not host.is_pinned():
-            raise ValueError("the Model Cache buffer must be pinned host memory")
+    def register(self, model_id: int, host, offs: Sequence[int], sizes: Sequence[int],
+                 fps: Optional[Sequence[int]] = None, stage_bytes: int = 2 << 30) -> RegisteredModel:
         if fps is None:
-            fps = fingerprint_host_buffer(host, offs, sizes, stage_bytes, self.stream_gather,
+            view, _, _ = _host_view(host)
+            fps = fingerprint_host_buffer(view, offs, sizes, stage_bytes, self.stream_gather,
                                           str(self.device))
         return RegisteredModel(model_id, host, offs, sizes, fps)
 

@@ -5,13 +5,18 @@ from typing import Dict, List, Optional
 import torch
 
 from . import synth
-from . import tangram as tg
-from .loader import RegisteredModel, ReusePool
+from .loader import HostArena, RegisteredModel, ReusePool
 
 
 class WorkloadRunner:
     """Materialises a workload's models in pinned host memory (the Model
-    Cache), registers them (GPU fingerprints) and replays its actions."""
+    Cache), registers them (GPU fingerprints) and replays its actions.
+
+    The measured models, and every setup model that shares tensors with them,
+    live in one cache image in which equal tensors are stored once.  Other
+    setup models (residents that only occupy the pool) get an image of their
+    own that is freed as soon as they have been loaded.
+    """
 
     def __init__(self, w: synth.Workload, device: str = "cuda:0", gen_device: Optional[str] = None,
                  log=None):
@@ -21,39 +26,83 @@ class WorkloadRunner:
         self.log = log or (lambda *_: None)
         self.pool = ReusePool(w.pool_bytes, w.align, device)
         self.models: Dict[str, RegisteredModel] = {}
-        self.host: Dict[str, torch.Tensor] = {}
+        self.arena: Optional[HostArena] = None
+        self._main_names = self._pick_main()
+        self._main_offs: Dict[str, List[int]] = {}
+        self._main_fps: Dict[int, int] = {}
+
+    def _pick_main(self) -> List[str]:
+        keys = set()
+        for name in self.w.loads:
+            keys.update(synth.content_key(t) for t in self.w.models[name].tensors if t.kind == "normal")
+        names = []
+        for act in self.w.setup:
+            if act[0] != "load" or act[1] in names:
+                continue
+            if any(t.kind == "normal" and synth.content_key(t) in keys
+                   for t in self.w.models[act[1]].tensors):
+                names.append(act[1])
+        return names + [n for n in self.w.loads if n not in names]
+
+    def host_numpy(self, name: str):
+        return self.models[name].host_tensor.numpy()
+
+    def _build_main(self) -> None:
+        t0 = time.time()
+        specs = [self.w.models[n] for n in self._main_names]
+        total, per_model, unique = synth.shared_layout(specs, self.w.align)
+        self.arena = HostArena(total)
+        for t, off in unique:
+            self.arena.tensor[off:off + t.nbytes].copy_(synth.tensor_bytes(t, self.gen_device))
+        # fingerprint every unique tensor once, then hand each model its rows
+        u_offs = [off for _, off in unique]
+        u_sizes = [t.nbytes for t, _ in unique]
+        u_fps = self.pool.register(0, self.arena, u_offs, u_sizes).fps
+        by_off = dict(zip(u_offs, u_fps))
+        for spec in specs:
+            offs = per_model[spec.name]
+            sizes = [t.nbytes for t in spec.tensors]
+            fps = [by_off[o] for o in offs]
+            self.models[spec.name] = RegisteredModel(spec.model_id, self.arena, offs, sizes, fps)
+        self.log("model cache: %s in one image of %.3f GB (%d unique tensors) in %.1f s"
+                 % (",".join(self._main_names), total / 1e9, len(unique), time.time() - t0))
 
     def materialise(self, name: str) -> RegisteredModel:
         if name in self.models:
             return self.models[name]
+        if name in self._main_names:
+            self._build_main()
+            return self.models[name]
         spec = self.w.models[name]
         t0 = time.time()
-        host = torch.empty(synth.host_bytes(spec, self.w.align), dtype=torch.uint8, pin_memory=True)
-        offs = synth.fill_host(spec, host, self.gen_device, self.w.align)
+        host = HostArena(synth.host_bytes(spec, self.w.align))
+        offs = synth.fill_host(spec, host.tensor, self.gen_device, self.w.align)
         sizes = [t.nbytes for t in spec.tensors]
         reg = self.pool.register(spec.model_id, host, offs, sizes)
         self.models[name] = reg
-        self.host[name] = host
         self.log("materialised %s: %d tensors, %.3f GB in %.1f s"
                  % (name, len(sizes), sum(sizes) / 1e9, time.time() - t0))
         return reg
 
     def drop_host(self, name: str) -> None:
-        """Forget a model's host image (its resident tensors stay in the pool)."""
-        self.models.pop(name, None)
-        self.host.pop(name, None)
+        """Forget a model's private host image (its tensors stay in the pool)."""
+        if name in self._main_names:
+            return
+        reg = self.models.pop(name, None)
+        if reg is not None and isinstance(reg.host, HostArena):
+            reg.host_tensor = None
+            reg.host.free()
 
-    def run_setup(self, keep_host: bool = True) -> None:
+    def run_setup(self) -> None:
         for act in self.w.setup:
             if act[0] == "load":
                 reg = self.materialise(act[1])
                 self.pool.load(reg)
                 self.log("setup: loaded %s" % act[1])
+                self.drop_host(act[1])
             else:
                 _, name, evict = act
                 self.pool.release(self.w.models[name].model_id, evict)
-                if not keep_host:
-                    self.drop_host(name)
 
     def load(self, name: str, confirm: bool = False, verify: bool = False):
         reg = self.materialise(name)
@@ -64,5 +113,9 @@ class WorkloadRunner:
 
     def close(self) -> None:
         self.pool.close()
+        for reg in self.models.values():
+            reg.host_tensor = None
         self.models.clear()
-        self.host.clear()
+        if self.arena is not None:
+            self.arena.free()
+            self.arena = None

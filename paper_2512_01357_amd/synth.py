@@ -342,6 +342,28 @@ def fill_host(model: ModelSpec, out: torch.Tensor, device: str = "cpu",
     return offs
 
 
+def shared_layout(models: Sequence[ModelSpec], align: int = 256):
+    """One Model Cache image for several models in which tensors with equal
+    content (see content_key) are stored once.  Returns (total bytes,
+    {model name: [offset per tensor]}, [(TensorSpec, offset)] of the unique
+    tensors in first-seen order)."""
+    at = 0
+    seen = {}
+    per_model = {}
+    unique = []
+    for m in models:
+        offs = []
+        for t in m.tensors:
+            key = content_key(t)
+            if key not in seen:
+                seen[key] = at
+                unique.append((t, at))
+                at += (t.nbytes + align - 1) // align * align
+            offs.append(seen[key])
+        per_model[m.name] = offs
+    return max(at, align), per_model, unique
+
+
 def content_key(spec: TensorSpec) -> Tuple:
     """Identity of a tensor's bytes: equal keys <=> equal bytes (for a given
     device).  Lets metadata-only tests stand in a fake fingerprint."""

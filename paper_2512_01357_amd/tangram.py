@@ -84,7 +84,7 @@ EXPORTS = [
     "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_fingerprint", "tg_compare",
     "tg_plan", "tg_plan_ops", "tg_plan_free", "tg_assemble", "tg_commit", "tg_release",
     "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
-    "tg_shutdown", "tg_strerror",
+    "tg_host_alloc", "tg_host_free", "tg_shutdown", "tg_strerror",
 ]
 
 
@@ -116,6 +116,8 @@ def lib() -> ctypes.CDLL:
             "tg_get_tuning": ([P(tg_tuning)], i32),
             "tg_set_profiling": ([ctypes.c_int], None),
             "tg_last_timing": ([P(tg_timing)], i32),
+            "tg_host_alloc": ([u64, P(vp)], i32),
+            "tg_host_free": ([vp], i32),
             "tg_shutdown": ([], None),
             "tg_strerror": ([i32], ctypes.c_char_p),
         }
@@ -285,6 +287,17 @@ def tg_last_timing() -> dict:
     t = tg_timing()
     _check(lib().tg_last_timing(ctypes.byref(t)), "tg_last_timing")
     return {n: getattr(t, n) for n, _ in tg_timing._fields_ if n != "reserved"}
+
+
+def tg_host_alloc(nbytes: int) -> int:
+    """Address of nbytes of pinned, device-mapped host memory."""
+    out = ctypes.c_void_p()
+    _check(lib().tg_host_alloc(nbytes, ctypes.byref(out)), "tg_host_alloc")
+    return int(out.value)
+
+
+def tg_host_free(ptr: int) -> None:
+    _check(lib().tg_host_free(ctypes.c_void_p(ptr)), "tg_host_free")
 
 
 def tg_shutdown() -> None:

@@ -43,9 +43,13 @@ def random_bytes(rnd: random.Random, n: int) -> bytes:
     return np.random.default_rng(rnd.getrandbits(32)).integers(0, 256, n, dtype=np.uint8).tobytes()
 
 
+# tile sizes in use: 256 lanes x 16 B x U (read kernels), 1024 lanes x 16 B x U (gather)
 TILE_U8 = 256 * 16 * 8
-LENGTHS = [0, 1, 7, 8, 9, 15, 16, 17, 31, 4095, 4096, 4097, TILE_U8 - 1, TILE_U8, TILE_U8 + 1,
-           TILE_U8 + 16, 3 * TILE_U8 + 4096 + 5, 10 * TILE_U8, (1 << 20) + 24, 5 * (1 << 20) + 13]
+TILE_COPY = 1024 * 16 * 8
+LENGTHS = [0, 1, 7, 8, 9, 15, 16, 17, 31, 4095, 4096, 4097, 8192, 16384 - 16, 16384, 16384 + 8,
+           TILE_U8 - 1, TILE_U8, TILE_U8 + 1, TILE_U8 + 16, 3 * TILE_U8 + 4096 + 5, 65536 + 24,
+           10 * TILE_U8, TILE_COPY - 16, TILE_COPY, TILE_COPY + 1, 2 * TILE_COPY + 40,
+           (1 << 20) + 24, 5 * (1 << 20) + 13]
 
 
 @pytest.mark.parametrize("unroll", [2, 4, 8, 16])
@@ -226,7 +230,8 @@ def test_load_small_models_ragged_sizes(gather_unroll):
         rnd = random.Random(31 + gather_unroll)
         b = Both(64 << 20)
         sizes = [1, 7, 16, 24, 255, 256, 257, 4096, 5000, TILE_U8 - 16, TILE_U8, TILE_U8 + 8,
-                 3 * TILE_U8 + 4096 + 5, (1 << 20) + 24, 3 * (1 << 20) + 1]
+                 3 * TILE_U8 + 4096 + 5, TILE_COPY // 4, TILE_COPY // 2 + 16, TILE_COPY - 8,
+                 TILE_COPY, TILE_COPY + 24, 2 * TILE_COPY, (1 << 20) + 24, 3 * (1 << 20) + 1]
         a = [random_bytes(rnd, n) for n in sizes]
         b.load(1, a)
         b.release(1)
@@ -236,7 +241,7 @@ def test_load_small_models_ragged_sizes(gather_unroll):
         assert sum(1 for op in plan.ops if op.kind == 0) == sum(1 for i in range(len(sizes)) if i % 3)
         b.release(1, evict=True)
         # third model lands in the holes model 1 left
-        m3 = [m2[i] for i in (14, 13, 3, 0)] + [random_bytes(rnd, 70000)]
+        m3 = [m2[i] for i in (20, 19, 14, 13, 3, 0)] + [random_bytes(rnd, 70000)]
         b.load(3, m3, verify=True)
         b.release(2, evict=True)
         b.release(3)
@@ -334,7 +339,7 @@ def run_workload_both(w, sample_check=None):
 
     def rows(name):
         reg = r.materialise(name)
-        host_np[name] = r.host[name].numpy()
+        host_np[name] = r.host_numpy(name)
         spec = w.models[name]
         want = [oracle.fingerprint(host_np[name][o:o + t.nbytes]) for t, o in zip(spec.tensors, reg.offs)]
         assert reg.fps == want, "fingerprints of %s" % name
