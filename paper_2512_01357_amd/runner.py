@@ -19,7 +19,7 @@ class WorkloadRunner:
     """
 
     def __init__(self, w: synth.Workload, device: str = "cuda:0", gen_device: Optional[str] = None,
-                 log=None):
+                 log=None, arena_budget: int = 56 << 30):
         self.w = w
         self.device = device
         self.gen_device = gen_device or device
@@ -28,6 +28,11 @@ class WorkloadRunner:
         self.models: Dict[str, RegisteredModel] = {}
         self.arena: Optional[HostArena] = None
         self._main_names = self._pick_main()
+        specs = [w.models[n] for n in self._main_names]
+        if w.streamed or synth.shared_layout(specs, w.align)[0] > arena_budget:
+            # too big to pin at once: every model gets a private image that
+            # lives only while it is being loaded
+            self._main_names = []
         self._main_offs: Dict[str, List[int]] = {}
         self._main_fps: Dict[int, int] = {}
 

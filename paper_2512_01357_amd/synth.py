@@ -68,6 +68,9 @@ class Workload:
     setup: List[tuple]
     loads: List[str]
     designated_shared: Dict[str, int] = field(default_factory=dict)
+    # True when the measured model is cut into parts that pass through the
+    # Model Cache one after the other (all parts together are one load)
+    streamed: bool = False
 
 
 def seed_for(cfg: int, model: int, k: int) -> int:
@@ -254,7 +257,22 @@ def workload_neox20b() -> Workload:
                     setup, ["M20"], {"M20": n_shared})
 
 
-def workload_llama70b(reuse: float, pool_bytes: int) -> Workload:
+def split_model(spec: ModelSpec, max_bytes: int, id_base: int) -> List[ModelSpec]:
+    """Cuts a model into parts of consecutive tensors, each at most max_bytes
+    (a Model Cache smaller than the model streams it part by part).  Part p is
+    a model of its own, named "<name>.p<p>", with id id_base + p."""
+    parts: List[List[TensorSpec]] = [[]]
+    size = 0
+    for t in spec.tensors:
+        if parts[-1] and size + t.nbytes > max_bytes:
+            parts.append([])
+            size = 0
+        parts[-1].append(t)
+        size += t.nbytes
+    return [ModelSpec("%s.p%d" % (spec.name, p), id_base + p, ts) for p, ts in enumerate(parts)]
+
+
+def workload_llama70b(reuse: float, pool_bytes: int, part_bytes: int = 48 * 10**9) -> Workload:
     """Config 5: 70B Llama-3-shaped model; a resident sibling holds the
     designated share of its tensors (0, 50 or 90 %)."""
     shapes = llama_tensors(8192, 80, 28672, 128256, 1024)
@@ -274,15 +292,21 @@ def workload_llama70b(reuse: float, pool_bytes: int) -> Workload:
     setup: List[tuple] = []
     sib = make_model("sib", 1, shapes, 5, 0, gains_one=True, subset=keep)
     if sib.tensors:
-        models["sib"] = sib
-        setup = [("load", "sib"), ("release", "sib", False)]
+        # the sibling reaches the pool in parts: the box cannot pin 127 GB at once
+        for part in split_model(sib, part_bytes, 100):
+            models[part.name] = part
+            setup += [("load", part.name), ("release", part.name, False)]
     m = make_model("M70", 2, shapes, 5, 1, gains_one=True,
                    share_from=sib if sib.tensors else None, shared=keep)
-    models["M70"] = m
+    loads = []
+    for part in split_model(m, part_bytes, 200):
+        models[part.name] = part
+        loads.append(part.name)
     n_shared = sum(1 for k, (nm, _, _) in enumerate(shapes) if keep(k, nm))
-    return Workload("llama3-70b-reuse%02d" % int(round(reuse * 100)),
-                    pool_bytes // 256 * 256, 256, models, setup, ["M70"],
-                    {"M70": n_shared})
+    w = Workload("llama3-70b-reuse%02d" % int(round(reuse * 100)),
+                 pool_bytes // 256 * 256, 256, models, setup, loads, {"M70": n_shared})
+    w.streamed = True
+    return w
 
 
 WORKLOADS = {

@@ -1,0 +1,109 @@
+"""Drives a synthetic workload through the HIP library and the CPU oracle side
+by side (GPU tests only).  Every oracle input is host bytes; nothing the
+library computes is fed to the oracle."""
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import torch
+
+import oracle
+from oracle import ReuseStoreOracle
+from paper_2512_01357_amd.runner import WorkloadRunner
+
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[gpu-test] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_fps(host_np, offs, sizes, threads=16):
+    """Oracle fingerprints of many tensors; the C loop releases the GIL, so a
+    thread per tensor is just a way to use the host's cores."""
+    uniq = sorted(set(zip(offs, sizes)))
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        vals = list(ex.map(lambda os_: oracle.fingerprint(host_np[os_[0]:os_[0] + os_[1]]), uniq))
+    table = dict(zip(uniq, vals))
+    return [table[(o, n)] for o, n in zip(offs, sizes)]
+
+
+def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
+    """Replays `w` on the library and on the oracle.
+
+    Fingerprints, plan rows, returned addresses and pool statistics are
+    compared for every tensor.  Assembled bytes: every slot is compared with
+    its host source (on the device, by torch.equal, an independent checker);
+    while a model is at most `image_limit` bytes the oracle also keeps its
+    own image of the pool and every slot is compared with it, beyond that the
+    oracle assembles every `sample_every`-th tensor (and the smallest and
+    largest) on its own and those are compared byte for byte.
+    """
+    r = WorkloadRunner(w, DEV, gen_device=DEV, log=say)
+    store = ReuseStoreOracle(w.pool_bytes, w.align)
+    small = all(m.nbytes <= image_limit for m in w.models.values())
+    plans = {}
+
+    def load(name):
+        reg = r.materialise(name)
+        host_np = r.host_numpy(name)
+        want = oracle_fps(host_np, reg.offs, reg.sizes)
+        assert reg.fps == want, "fingerprints of %s" % name
+        rows = list(zip(reg.sizes, want, reg.offs))
+        oplan = store.plan(w.models[name].model_id, rows, host_np if small else None)
+        ptrs, info = r.load(name, verify=True)
+        assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops], name
+        assert info["reused_bytes"] == oplan.reused_bytes
+        assert info["transfer_bytes"] == oplan.transfer_bytes
+        dsts = store.assemble(oplan, host_np if small else None)
+        assert ptrs == [r.pool.base + d for d in dsts]
+        host_t = r.models[name].host_tensor
+        n = len(rows)
+        by_size = sorted(range(n), key=lambda k: rows[k][0])
+        sampled = set(range(0, n, sample_every)) | {by_size[0], by_size[-1]}
+        for k, (op, (nbytes, _f, off)) in enumerate(zip(oplan.ops, rows)):
+            slot = r.pool.slab[op.dst_off:op.dst_off + nbytes]
+            assert torch.equal(slot, host_t[off:off + nbytes].to(DEV)), (name, k)
+            if small:
+                assert slot.cpu().numpy().tobytes() == store.image[op.dst_off].tobytes(), (name, k)
+            elif k in sampled:
+                mine = np.empty(nbytes, dtype=np.uint8)
+                oracle.copy_bytes(mine, host_np[off:off + nbytes])       # the oracle's assemble
+                assert oracle.bytes_equal(slot.cpu().numpy(), mine), (name, k)
+        a, b = r.pool.stats(), store.stats()
+        for key, v in b.items():
+            assert a[key] == v, key
+        if after_load is not None:
+            after_load(name, oplan, r)
+        r.drop_host(name)
+        return oplan
+
+    for act in w.setup:
+        if act[0] == "load":
+            load(act[1])
+            say("setup %s checked" % act[1])
+        else:
+            r.release(act[1], act[2])
+            store.release(w.models[act[1]].model_id, act[2])
+    before = store.stats()
+    if w.streamed:
+        for name in w.loads:
+            plans[name] = load(name)
+            say("part %s checked" % name)
+        for name in w.loads:
+            r.release(name, True)
+            store.release(w.models[name].model_id, True)
+    else:
+        for name in w.loads:
+            plans[name] = load(name)
+            say("load %s checked" % name)
+            r.release(name, True)
+            store.release(w.models[name].model_id, True)
+    assert store.stats() == before
+    a = r.pool.stats()
+    for key, v in before.items():
+        assert a[key] == v, key
+    r.close()
+    torch.cuda.empty_cache()
+    return plans, before

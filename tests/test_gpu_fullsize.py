@@ -1,0 +1,48 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration
+bench.py times (default tuning, verify on): fingerprints and plans of every
+tensor against the oracle, every assembled slot against its host source, and
+oracle-assembled samples byte for byte."""
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from gpu_harness import run_workload_both, say  # noqa: E402
+from paper_2512_01357_amd import synth  # noqa: E402
+
+
+def test_llama_7b_family_full_size():
+    say("full size: llama 7B family")
+    w = synth.workload_llama7b()
+    plans, _ = run_workload_both(w)
+    for v in ("v1", "v2", "v3"):
+        p = plans[v]
+        assert p.reused_bytes + p.transfer_bytes == w.models[v].nbytes
+        assert 0.51 < p.reused_bytes / w.models[v].nbytes < 0.53
+
+
+def test_neox_20b_fragmented_pool_full_size():
+    say("full size: NeoX 20B into a fragmented 200 GB pool")
+    w = synth.workload_neox20b()
+    plans, before = run_workload_both(w)
+    p = plans["M20"]
+    assert before["n_free_regions"] >= 5
+    assert p.reused_bytes + p.transfer_bytes == w.models["M20"].nbytes
+    assert 0.29 < p.reused_bytes / w.models["M20"].nbytes < 0.32
+    # the load used the holes, not only the tail of the pool
+    assert min(op.dst_off for op in p.ops) < before["capacity"] - before["largest_free"]
+
+
+@pytest.mark.parametrize("reuse", [0.5])
+def test_llama3_70b_full_size(reuse):
+    say("full size: Llama-3 70B, reuse %.0f %%" % (reuse * 100))
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    w = synth.workload_llama70b(reuse, int(free - (16 << 30)))
+    plans, _ = run_workload_both(w)
+    total = sum(w.models[n].nbytes for n in w.loads)
+    reused = sum(plans[n].reused_bytes for n in w.loads)
+    assert abs(reused / total - reuse) < 0.02

@@ -21,6 +21,7 @@ from paper_2512_01357_amd import synth  # noqa: E402
 from paper_2512_01357_amd import tangram as tg  # noqa: E402
 from paper_2512_01357_amd.loader import ReusePool  # noqa: E402
 from paper_2512_01357_amd.runner import WorkloadRunner  # noqa: E402
+from gpu_harness import run_workload_both  # noqa: E402
 from recipes import build, read_pairs  # noqa: E402
 from test_oracle_fingerprint import colliding_pair  # noqa: E402
 
@@ -331,62 +332,17 @@ def test_stale_and_no_space_on_the_device_path():
     pool.close()
 
 
-def run_workload_both(w, sample_check=None):
-    """Replays a workload on the library and on the oracle (with images)."""
-    r = WorkloadRunner(w, DEV, gen_device=DEV, log=say)
-    store = ReuseStoreOracle(w.pool_bytes, w.align)
-    host_np = {}
-
-    def rows(name):
-        reg = r.materialise(name)
-        host_np[name] = r.host_numpy(name)
-        spec = w.models[name]
-        want = [oracle.fingerprint(host_np[name][o:o + t.nbytes]) for t, o in zip(spec.tensors, reg.offs)]
-        assert reg.fps == want, "fingerprints of %s" % name
-        return [(n, f, o) for n, f, o in zip(reg.sizes, reg.fps, reg.offs)]
-
-    def load(name):
-        rws = rows(name)
-        oplan = store.plan(w.models[name].model_id, rws, host_np[name])
-        ptrs, info = r.load(name, verify=True)
-        assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops]
-        dsts = store.assemble(oplan, host_np[name])
-        assert ptrs == [r.pool.base + d for d in dsts]
-        for op, (n, f, o) in zip(oplan.ops, rws):
-            got = r.pool.pool and r.pool.slab[op.dst_off:op.dst_off + n].cpu().numpy()
-            assert got.tobytes() == store.image[op.dst_off].tobytes()
-            assert got.tobytes() == host_np[name][o:o + n].tobytes()
-        return oplan
-
-    for act in w.setup:
-        if act[0] == "load":
-            load(act[1])
-        else:
-            r.release(act[1], act[2])
-            store.release(w.models[act[1]].model_id, act[2])
-    plans = {}
-    for name in w.loads:
-        plans[name] = load(name)
-        a, b = r.pool.stats(), store.stats()
-        for k, v in b.items():
-            assert a[k] == v, k
-        r.release(name, True)
-        store.release(w.models[name].model_id, True)
-    r.close()
-    return plans
-
-
 def test_workload_tiny_gpt_pair():
     say("workload tiny")
     w = synth.workload_tiny()
-    plans = run_workload_both(w)
+    plans, _ = run_workload_both(w)
     assert sum(1 for op in plans["B"].ops if op.kind == 0) == 39
 
 
 def test_workload_gpt_1_3b():
     say("workload gpt1b")
     w = synth.workload_gpt1b()
-    plans = run_workload_both(w)
+    plans, _ = run_workload_both(w, image_limit=4 << 30)
     p = plans["M"]
     assert p.reused_bytes + p.transfer_bytes == w.models["M"].nbytes
     assert 0.45 < p.reused_bytes / w.models["M"].nbytes < 0.60
