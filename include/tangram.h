@@ -53,6 +53,9 @@ typedef int32_t tg_status;
 
 /* tg_plan flags */
 #define TG_PLAN_CONFIRM   1u   /* compare bytes of every fingerprint hit before trusting it */
+#define TG_PLAN_EVICT     2u   /* Stage 1: evict retained tensors by ascending cost when free bytes are short */
+#define TG_PLAN_MERGE     4u   /* Stage 2: when best fit fails, pack by partitions and merge free regions */
+#define TG_PLAN_ALIAS     8u   /* a hit is used where it lies (no copy, no new slot) */
 /* tg_assemble flags */
 #define TG_ASSEMBLE_VERIFY 1u  /* fingerprint every assembled slot and compare with the descriptor */
 /* tg_release flags */
@@ -110,6 +113,27 @@ typedef struct {
     uint64_t nbytes;
 } tg_plan_op;
 
+/* A resident tensor that Stage 2 moves to merge free regions. */
+typedef struct {
+    uint64_t old_off;
+    uint64_t new_off;
+    uint64_t nbytes;
+} tg_move;
+
+/* Totals of a plan. */
+typedef struct {
+    uint32_t n_tensors;
+    uint32_t n_evictions;     /* tensors Stage 1 evicts */
+    uint32_t n_moves;         /* tensors Stage 2 moves */
+    uint32_t alias;           /* 1 if the plan was made with TG_PLAN_ALIAS */
+    uint64_t reused_bytes;    /* bytes found resident */
+    uint64_t transfer_bytes;  /* bytes that come from the host */
+    uint64_t copy_bytes;      /* bytes the gather kernel copies (0 in alias mode) */
+    uint64_t evicted_bytes;   /* slot bytes Stage 1 frees */
+    uint64_t moved_bytes;     /* bytes of the tensors Stage 2 moves */
+    uint64_t merge_bound;     /* Algorithm 1's merge cost M (an upper bound on moved slot bytes) */
+} tg_plan_summary;
+
 typedef struct {
     uint64_t capacity;        /* pool size */
     uint64_t free_bytes;      /* sum of free regions */
@@ -134,7 +158,11 @@ typedef struct {
     float    plan_host_ms;    /* host time of the last tg_plan (steady clock) */
     uint64_t fingerprint_bytes, compare_bytes, gather_bytes, h2d_bytes, verify_bytes;
     uint32_t h2d_copies;      /* hipMemcpyAsync calls issued by the last tg_assemble */
-    uint32_t reserved;
+    uint32_t move_launches;   /* copy launches the merge moves of the last tg_assemble took */
+    float    move_ms;         /* first to last merge-move launch of the last tg_assemble */
+    float    reserved;
+    uint64_t move_bytes;      /* bytes of the tensors moved */
+    uint64_t move_traffic_bytes; /* bytes read + written by the move launches (staged stretches count twice) */
 } tg_timing;
 
 /*
@@ -181,34 +209,63 @@ tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, vo
 
 /*
  * Plan the load of `model` into `pool`.  (Section 3.1: search the Tensor
- * Mapping for the model's tensors; Section 3.2: best-fit allocation.)
+ * Mapping for the model's tensors, evict tensors of inactive models if space
+ * is short; Section 3.2: best-fit allocation, Stage 1 minimal-cost eviction,
+ * Stage 2 Partitioned-Gain Packing.)
  *
  *  match    key (fp, nbytes) against the tensors resident when the call
- *           starts (active or retained); among equal keys the lowest pool
+ *           starts (in use or retained); among equal keys the lowest pool
  *           offset wins.  With TG_PLAN_CONFIRM every candidate is compared
  *           with the incoming bytes (read from host_base through its device
  *           mapping by the compare kernel on `stream`) and candidates whose
  *           bytes differ are dropped.  A tensor with a surviving candidate is
  *           a TG_OP_REUSE, any other a TG_OP_H2D.
- *  allocate every tensor gets a fresh slot of roundup(nbytes, align) bytes:
- *           largest slot first (ties: lower index first), each into the
+ *  slots    by default every tensor gets a fresh slot of roundup(nbytes,
+ *           align) bytes and a hit is copied into it.  With TG_PLAN_ALIAS a
+ *           hit is used where it lies (dst_off == src_off, the row becomes
+ *           shared between the models that own it) and only misses get slots.
+ *  evict    with TG_PLAN_EVICT, when the free bytes are fewer than the slots
+ *           need: tensors that no running model uses and that this plan does
+ *           not read are evicted in ascending cost c = p * (nbytes / b) * alpha
+ *           of their model (Eq. 2; see tg_set_model_cost; a tensor several
+ *           models own costs the sum; ties: lower offset) until enough bytes
+ *           are free.
+ *  allocate largest slot first (ties: lower index first), each into the
  *           smallest free region that holds it (ties: lowest offset), at the
  *           region's low end.
+ *  merge    with TG_PLAN_MERGE, when best fit fails although enough bytes are
+ *           free: Algorithm 1 splits the Region List at resident tensors
+ *           (largest first) wherever its two-bin packing test lets the tensors
+ *           be divided over the two sides, by free bytes; each final subspace
+ *           takes its tensors by best fit if it can, else its resident tensors
+ *           are slid to its low end (tg_plan_moves) and the tensors placed in
+ *           the merged free tail.  Tensors in use by a running model never
+ *           move; they split the pool beforehand.
  *
  * The pool is not modified.  *out receives a plan bound to the pool's current
- * generation.  TG_ERR_INVALID: null arguments, n_tensors == 0, a zero-length
- * tensor, src_off + nbytes > host_bytes, model_id active in the pool.
- * TG_ERR_NOSPACE: some tensor has no free region that holds it.
- * `stream` is used only with TG_PLAN_CONFIRM.
+ * generation.  TG_ERR_INVALID: null arguments, unknown flag bits, n_tensors ==
+ * 0, a zero-length tensor, src_off + nbytes > host_bytes, model_id running in
+ * the pool.  TG_ERR_NOSPACE: the tensors cannot be placed with the stages
+ * that the flags allow.  `stream` is used only with TG_PLAN_CONFIRM.
  */
 tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
                   tg_load_plan **out);
 
 /* Rows of the plan, one per tensor in the model's order, and byte totals:
- * reused_bytes + transfer_bytes == sum of nbytes.  *ops points into the plan
- * and lives until tg_plan_free.  Any out pointer may be NULL. */
+ * reused_bytes + transfer_bytes == sum of nbytes.  A REUSE row's src_off is
+ * where the resident copy lies once the plan's moves have run.  *ops points
+ * into the plan and lives until tg_plan_free.  Any out pointer may be NULL. */
 tg_status tg_plan_ops(const tg_load_plan *plan, const tg_plan_op **ops, uint32_t *n,
                       uint64_t *reused_bytes, uint64_t *transfer_bytes);
+
+/* Totals of the plan.  out [host]. */
+tg_status tg_plan_info(const tg_load_plan *plan, tg_plan_summary *out);
+
+/* The tensors Stage 2 moves, in the order the moves are carried out, and the
+ * pool offsets of the tensors Stage 1 evicts, in eviction order.  The arrays
+ * live in the plan until tg_plan_free. */
+tg_status tg_plan_moves(const tg_load_plan *plan, const tg_move **moves, uint32_t *n);
+tg_status tg_plan_evictions(const tg_load_plan *plan, const uint64_t **offsets, uint32_t *n);
 
 void tg_plan_free(tg_load_plan *plan);
 
@@ -217,12 +274,17 @@ void tg_plan_free(tg_load_plan *plan);
  * Tensor Mapping, return the GPU address of every tensor; Section 4: tensor
  * transfers are grouped into large copies.)
  *
- * One gather kernel on stream_gather copies every reused tensor into its
- * slot; at the same time the missing tensors are copied from the model's
- * pinned host buffer with hipMemcpyAsync on stream_h2d (copies that are
- * adjacent on both sides are merged into one).  The call waits for both
- * streams, then commits: slots become allocated regions, one active Tensor
- * Mapping row per tensor is added, the generation advances.
+ * If the plan moves resident tensors, the moves run first on stream_gather,
+ * as copy launches whose reads and writes never meet (a stretch that shifts
+ * by less than 32 MiB goes through a 128 MiB staging buffer of the library);
+ * stream_h2d waits for them.  Then one gather kernel on stream_gather copies
+ * every reused tensor into its slot (none in alias mode); at the same time
+ * the missing tensors are copied from the model's pinned host buffer with
+ * hipMemcpyAsync on stream_h2d (copies that are adjacent on both sides are
+ * merged into one).  The call waits for both streams, then commits: evicted
+ * rows disappear, moved rows change address, slots become allocated regions,
+ * one Tensor Mapping row per new slot is added (aliased rows gain an owner),
+ * the model's rows count as in use, the generation advances.
  * out_dev_ptrs [host], if not NULL, receives n_tensors [device] addresses.
  * With TG_ASSEMBLE_VERIFY the slots are fingerprinted (one launch on
  * stream_gather) before committing and TG_ERR_CORRUPT is returned, without
@@ -242,12 +304,25 @@ tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs);
 
 /*
  * The model instance ends.  (Section 3.1: tensors of inactive models stay
- * resident and reusable until evicted.)  flags == 0 marks the model's rows
- * inactive; their bytes stay and keep matching.  TG_RELEASE_EVICT removes the
- * rows and frees their regions, merging each with free neighbours.
- * TG_ERR_NOTFOUND if the pool holds nothing of model_id.
+ * resident and reusable until evicted.)  flags == 0: the model's rows no
+ * longer count as in use by it; their bytes stay and keep matching.
+ * TG_RELEASE_EVICT: the model also gives up its rows; those that no other
+ * model owns are removed and their regions freed and merged with free
+ * neighbours.  TG_ERR_NOTFOUND if the pool holds nothing of model_id.
  */
 tg_status tg_release(tg_pool *pool, uint64_t model_id, uint32_t flags);
+
+/*
+ * Eviction-cost parameters of a model (Eq. 2): miss_prob = p_m, the
+ * probability that a tensor of the model is missed once evicted; load_bw =
+ * b_m, the bandwidth it would be reloaded at; alpha = alpha_m, the model's
+ * latency sensitivity (1 by default, smaller for tolerant models).  May be set
+ * before the model is ever loaded; unset models use 1, 1, 1.  How p_m is
+ * estimated is the caller's policy (the paper does not fix it).
+ * TG_ERR_INVALID unless miss_prob >= 0, load_bw > 0, alpha >= 0.
+ */
+tg_status tg_set_model_cost(tg_pool *pool, uint64_t model_id, double miss_prob, double load_bw,
+                            double alpha);
 
 /*
  * Bytes of `model` that a load would not have to transfer: the sum of nbytes

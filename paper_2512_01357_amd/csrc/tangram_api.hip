@@ -15,7 +15,7 @@
 #include "reuse_store.h"
 
 struct tg_pool { tg::ReuseStore store; tg_pool(uint64_t b, uint64_t c, uint32_t a) : store(b, c, a) {} };
-struct tg_load_plan { tg::Plan plan; std::vector<tg_plan_op> rows; };
+struct tg_load_plan { tg::Plan plan; std::vector<tg_plan_op> rows; std::vector<tg_move> move_rows; };
 
 namespace {
 
@@ -31,6 +31,13 @@ tg_tuning g_tune = {4, 2, 8, 2, 4, 2, 0};
 bool g_profiling = false;
 tg_timing g_timing = {};
 
+// A move whose source and destination overlap goes through this much staging at a time.
+constexpr size_t kBounceBytes = size_t(128) << 20;
+// A stretch of moves whose first byte shifts by at least this much is copied
+// straight (up to that many bytes per launch); below it launches would be too
+// small to be worth their launch cost and the stretch is staged.
+constexpr uint64_t kDirectShift = uint64_t(32) << 20;
+
 // Library-owned scratch: one pinned staging buffer and one device buffer that
 // hold a launch's descriptor table, tile prefix and result words.
 struct Scratch {
@@ -38,7 +45,8 @@ struct Scratch {
     void *h = nullptr, *d = nullptr;
     size_t cap = 0;
     int cu_count = 0;
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    void *bounce = nullptr;             // staging for moves whose source and destination overlap
 
     tg_status init() {
         if (cu_count != 0) return TG_OK;
@@ -68,8 +76,14 @@ struct Scratch {
         h = d = nullptr;
         cap = 0;
     }
+    tg_status ensure_bounce() {
+        if (bounce) return TG_OK;
+        if (hipMalloc(&bounce, kBounceBytes) != hipSuccess) { bounce = nullptr; (void)hipGetLastError(); return TG_ERR_NOMEM; }
+        return TG_OK;
+    }
     void shutdown() {
         release_buffers();
+        if (bounce) { (void)hipFree(bounce); bounce = nullptr; }
         for (auto &e : ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
         cu_count = 0;
     }
@@ -212,6 +226,69 @@ tg_status compare_locked(const tg_pair *pairs, u32 n, uint32_t *out_differs, hip
     return TG_OK;
 }
 
+// Merge moves as copy launches (Section 3.2, Stage 2).  Moves arrive in
+// execution order: ascending addresses, each shifting its tensor towards lower
+// addresses inside its own subspace.  Seen as one stream of bytes, a byte's
+// destination lies below its source, and below the source of every later byte,
+// so launches that run one after the other on a stream never overwrite bytes
+// that are still to be read.  Inside one launch reads and writes are
+// concurrent, so every destination must lie below the first source the launch
+// reads: a stretch whose first byte shifts by d can be copied straight, up to d
+// bytes per launch.  When d is small the stretch is staged instead: one launch
+// gathers up to kBounceBytes into the staging buffer, the next writes them out.
+tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
+                              std::vector<std::vector<tgk::Copy>> &launches, u64 &traffic) {
+    traffic = 0;
+    const u64 bounce = u64(reinterpret_cast<uintptr_t>(g_scratch.bounce));
+    size_t i = 0;
+    uint64_t done = 0;                      // bytes of moves[i] already scheduled
+    while (i < moves.size()) {
+        const tg::Move &f = moves[i];
+        if (f.new_off >= f.old_off || f.nbytes == 0) return TG_ERR_INVALID;
+        const uint64_t src0 = f.old_off + done, dst0 = f.new_off + done;
+        std::vector<tgk::Copy> in, out;
+        if (src0 - dst0 >= kDirectShift) {
+            while (i < moves.size()) {
+                const tg::Move &m = moves[i];
+                if (m.new_off >= m.old_off || m.nbytes == 0) return TG_ERR_INVALID;
+                const uint64_t d = m.new_off + done, s = m.old_off + done, left = m.nbytes - done;
+                if (d < dst0 || d >= src0) break;           // would write where this launch reads
+                uint64_t len = std::min<uint64_t>(left, src0 - d);
+                if (len < left) len &= ~uint64_t(15);
+                if (len == 0) break;
+                in.push_back(tgk::Copy{base + d, base + s, len});
+                traffic += 2 * len;
+                done += len;
+                if (done < m.nbytes) break;                 // cut short: the launch is full
+                ++i;
+                done = 0;
+            }
+        } else {
+            uint64_t staged = 0;
+            while (i < moves.size() && staged < kBounceBytes) {
+                const tg::Move &m = moves[i];
+                if (m.new_off >= m.old_off || m.nbytes == 0) return TG_ERR_INVALID;
+                const uint64_t d = m.new_off + done, s = m.old_off + done, left = m.nbytes - done;
+                uint64_t len = std::min<uint64_t>(left, kBounceBytes - staged);
+                if (len < left) len &= ~uint64_t(15);
+                if (len == 0) break;
+                in.push_back(tgk::Copy{bounce + staged, base + s, len});
+                out.push_back(tgk::Copy{base + d, bounce + staged, len});
+                staged += (len + 15) & ~uint64_t(15);
+                traffic += 4 * len;
+                done += len;
+                if (done < m.nbytes) break;
+                ++i;
+                done = 0;
+            }
+        }
+        if (in.empty()) return TG_ERR_INVALID;
+        launches.push_back(std::move(in));
+        if (!out.empty()) launches.push_back(std::move(out));
+    }
+    return TG_OK;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 tg_status check_model(const tg_model_desc *m, std::vector<tg::TensorIn> &tensors) {
@@ -295,6 +372,7 @@ tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, vo
 tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
                   tg_load_plan **out) {
     if (!pool || !out) return TG_ERR_INVALID;
+    if (flags & ~(TG_PLAN_CONFIRM | TG_PLAN_EVICT | TG_PLAN_MERGE | TG_PLAN_ALIAS)) return TG_ERR_INVALID;
     const auto t0 = std::chrono::steady_clock::now();
     std::vector<tg::TensorIn> tensors;
     tg_status rc = check_model(model, tensors);
@@ -305,13 +383,13 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
     if (confirm && !model->host_base) return TG_ERR_INVALID;
 
     const size_t n = tensors.size();
-    std::vector<uint64_t> src(n, UINT64_MAX);
-    std::vector<uint64_t> cand;
+    std::vector<uint64_t> hits(n, 0);
+    std::vector<std::pair<uint64_t, uint64_t>> cand;      // (offset, entry id), ascending offset
     if (!confirm) {
         // Section 3.1: a tensor found in the Tensor Mapping is reused.
         for (size_t k = 0; k < n; ++k) {
             store.candidates(tensors[k].fp, tensors[k].nbytes, cand);
-            if (!cand.empty()) src[k] = cand.front();
+            if (!cand.empty()) hits[k] = cand.front().second;
         }
     } else {
         // Every candidate of every tensor is compared with the incoming bytes
@@ -322,17 +400,17 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
             return TG_ERR_INVALID;
         }
         std::vector<tg_pair> pairs;
-        std::vector<std::pair<size_t, uint64_t>> who;   // (tensor, candidate offset)
+        std::vector<std::pair<size_t, uint64_t>> who;   // (tensor, candidate entry)
         for (size_t k = 0; k < n; ++k) {
             store.candidates(tensors[k].fp, tensors[k].nbytes, cand);
-            for (uint64_t off : cand) {
+            for (const auto &c : cand) {
                 tg_pair p;
-                p.a = reinterpret_cast<const void *>(uintptr_t(store.base() + off));
+                p.a = reinterpret_cast<const void *>(uintptr_t(store.base() + c.first));
                 p.b = static_cast<const char *>(host_dev) + tensors[k].src_off;
                 p.nbytes = tensors[k].nbytes;
                 if (!aligned16(p.b)) return TG_ERR_INVALID;
                 pairs.push_back(p);
-                who.push_back({k, off});
+                who.push_back({k, c.second});
             }
         }
         if (!pairs.empty()) {
@@ -341,7 +419,7 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
             rc = compare_locked(pairs.data(), u32(pairs.size()), differs.data(), static_cast<hipStream_t>(stream));
             if (rc != TG_OK) return rc;
             for (size_t i = 0; i < pairs.size(); ++i)
-                if (!differs[i] && src[who[i].first] == UINT64_MAX) src[who[i].first] = who[i].second;
+                if (!differs[i] && hits[who[i].first] == 0) hits[who[i].first] = who[i].second;
         }
     }
 
@@ -350,12 +428,17 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
     lp->plan.model_id = model->model_id;
     lp->plan.host_base = model->host_base;
     lp->plan.host_bytes = model->host_bytes;
-    const tg::Status ps = store.place(tensors, src, lp->plan);
+    const tg::Status ps = store.plan(tensors, hits, flags, lp->plan);
     if (ps != tg::OK) { delete lp; return tg_status(ps); }
     lp->rows.resize(n);
     for (size_t k = 0; k < n; ++k) {
         const tg::Op &op = lp->plan.ops[k];
         lp->rows[k] = tg_plan_op{op.kind, 0u, op.dst_off, op.src_off, op.nbytes};
+    }
+    lp->move_rows.resize(lp->plan.moves.size());
+    for (size_t i = 0; i < lp->plan.moves.size(); ++i) {
+        const tg::Move &m = lp->plan.moves[i];
+        lp->move_rows[i] = tg_move{m.old_off, m.new_off, m.nbytes};
     }
     *out = lp;
     if (g_profiling)
@@ -370,6 +453,36 @@ tg_status tg_plan_ops(const tg_load_plan *plan, const tg_plan_op **ops, uint32_t
     if (n) *n = uint32_t(plan->rows.size());
     if (reused_bytes) *reused_bytes = plan->plan.reused_bytes;
     if (transfer_bytes) *transfer_bytes = plan->plan.transfer_bytes;
+    return TG_OK;
+}
+
+tg_status tg_plan_info(const tg_load_plan *plan, tg_plan_summary *out) {
+    if (!plan || !out) return TG_ERR_INVALID;
+    const tg::Plan &p = plan->plan;
+    out->n_tensors = uint32_t(p.ops.size());
+    out->n_evictions = uint32_t(p.evict.size());
+    out->n_moves = uint32_t(p.moves.size());
+    out->alias = p.alias ? 1u : 0u;
+    out->reused_bytes = p.reused_bytes;
+    out->transfer_bytes = p.transfer_bytes;
+    out->copy_bytes = p.copy_bytes;
+    out->evicted_bytes = p.evicted_bytes;
+    out->moved_bytes = p.moved_bytes;
+    out->merge_bound = p.merge_bound;
+    return TG_OK;
+}
+
+tg_status tg_plan_moves(const tg_load_plan *plan, const tg_move **moves, uint32_t *n) {
+    if (!plan) return TG_ERR_INVALID;
+    if (moves) *moves = plan->move_rows.data();
+    if (n) *n = uint32_t(plan->move_rows.size());
+    return TG_OK;
+}
+
+tg_status tg_plan_evictions(const tg_load_plan *plan, const uint64_t **offsets, uint32_t *n) {
+    if (!plan) return TG_ERR_INVALID;
+    if (offsets) *offsets = plan->plan.evict_offs.data();
+    if (n) *n = uint32_t(plan->plan.evict_offs.size());
     return TG_OK;
 }
 
@@ -404,6 +517,18 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         if (rc != TG_OK) return rc;
     }
 
+    // ---- merge moves (Section 3.2, Stage 2), cut into launches whose reads and
+    // writes do not meet
+    std::vector<std::vector<tgk::Copy>> launches;
+    u64 move_traffic = 0;
+    if (!pl.moves.empty()) {
+        tg_status rc = g_scratch.ensure_bounce();
+        if (rc != TG_OK) return rc;
+        rc = build_move_launches(pl.moves, base, launches, move_traffic);
+        if (rc != TG_OK) return rc;
+    }
+    const size_t n_move_launches = launches.size();
+
     // Host-to-device list, in destination order; copies adjacent on both sides
     // (the slot padding included) are merged into one (Section 4 groups
     // adjacent tensors into large copies).
@@ -417,8 +542,10 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         (void)hipGetLastError();
         host_dev = nullptr;
     }
-    for (const tg::Op &op : pl.ops) {
+    for (size_t k = 0; k < pl.ops.size(); ++k) {
+        const tg::Op &op = pl.ops[k];
         if (op.kind == 0) {
+            if (pl.alias) continue;                      // used where it lies: nothing to copy
             copies.push_back(tgk::Copy{base + op.dst_off, base + op.src_off, op.nbytes});
         } else if (host_dev && op.nbytes <= small &&
                    ((uintptr_t(host_dev) + op.src_off) & 15u) == 0) {
@@ -442,30 +569,64 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         }
         merged.push_back(c);
     }
+    u64 gather_bytes = 0;
+    for (const auto &c : copies) gather_bytes += c.nbytes;
+    if (!copies.empty()) launches.push_back(copies);
+
+    // ---- one table upload for every copy launch of this call
+    const u32 U = pick_u(g_tune.gather_unroll);
+    const u64 tile = tile_for(tgk::kCopyThreads, U);
+    struct Placed { size_t desc_off, prefix_off; u32 n, tiles; };
+    std::vector<Placed> placed(launches.size());
+    size_t table_bytes = 0;
+    for (size_t i = 0; i < launches.size(); ++i) {
+        const TableLayout L = table_layout(launches[i].size(), sizeof(tgk::Copy), 0);
+        placed[i].desc_off = table_bytes + L.desc_off;
+        placed[i].prefix_off = table_bytes + L.prefix_off;
+        placed[i].n = u32(launches[i].size());
+        table_bytes += L.total;
+    }
+    if (!launches.empty()) {
+        tg_status rc = g_scratch.ensure(table_bytes);
+        if (rc != TG_OK) return rc;
+        char *h = static_cast<char *>(g_scratch.h);
+        for (size_t i = 0; i < launches.size(); ++i) {
+            std::memcpy(h + placed[i].desc_off, launches[i].data(), launches[i].size() * sizeof(tgk::Copy));
+            u32 *hp = reinterpret_cast<u32 *>(h + placed[i].prefix_off);
+            if (!fill_prefix(hp, &launches[i][0].nbytes, sizeof(tgk::Copy) / 8, launches[i].size(), tile))
+                return TG_ERR_INVALID;
+            placed[i].tiles = hp[launches[i].size()];
+        }
+        TG_HIP(hipMemcpyAsync(g_scratch.d, g_scratch.h, table_bytes, hipMemcpyHostToDevice, sg));
+    }
+    auto launch_copy = [&](size_t i) -> tg_status {
+        if (placed[i].tiles == 0) return TG_OK;
+        char *d = static_cast<char *>(g_scratch.d);
+        const u32 grid = grid_for(placed[i].tiles, g_tune.gather_wgs_per_cu);
+        const u32 run = run_for(placed[i].tiles, grid);
+        TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU><<<dim3(grid), dim3(tgk::kCopyThreads), 0, sg>>>(
+                        reinterpret_cast<const tgk::Copy *>(d + placed[i].desc_off),
+                        reinterpret_cast<const u32 *>(d + placed[i].prefix_off), placed[i].n, run));
+        TG_HIP(hipGetLastError());
+        return TG_OK;
+    };
+
+    // ---- moves first (stream A); nothing may land in the pool before they are done
+    if (n_move_launches > 0) {
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[4], sg));
+        for (size_t i = 0; i < n_move_launches; ++i) {
+            const tg_status rc = launch_copy(i);
+            if (rc != TG_OK) return rc;
+        }
+        TG_HIP(hipEventRecord(g_scratch.ev[5], sg));
+        if (sh != sg) TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[5], 0));
+    }
 
     // ---- gather launch (stream A)
-    u64 gather_bytes = 0;
-    u32 gather_tiles = 0;
     if (!copies.empty()) {
-        const u32 n = u32(copies.size());
-        const u32 U = pick_u(g_tune.gather_unroll);
-        const TableLayout L = table_layout(n, sizeof(tgk::Copy), 0);
-        tg_status rc = g_scratch.ensure(L.total);
-        if (rc != TG_OK) return rc;
-        char *h = static_cast<char *>(g_scratch.h), *d = static_cast<char *>(g_scratch.d);
-        std::memcpy(h + L.desc_off, copies.data(), n * sizeof(tgk::Copy));
-        u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
-        if (!fill_prefix(hp, &copies[0].nbytes, sizeof(tgk::Copy) / 8, n, tile_for(tgk::kCopyThreads, U))) return TG_ERR_INVALID;
-        gather_tiles = hp[n];
-        for (const auto &c : copies) gather_bytes += c.nbytes;
-        TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, sg));
-        const u32 grid = grid_for(gather_tiles, g_tune.gather_wgs_per_cu);
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], sg));
-        const u32 run = run_for(gather_tiles, grid);
-        TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU><<<dim3(grid), dim3(tgk::kCopyThreads), 0, sg>>>(
-                        reinterpret_cast<const tgk::Copy *>(d + L.desc_off),
-                        reinterpret_cast<const u32 *>(d + L.prefix_off), n, run));
-        TG_HIP(hipGetLastError());
+        const tg_status rc = launch_copy(launches.size() - 1);
+        if (rc != TG_OK) return rc;
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], sg));
     }
 
@@ -495,6 +656,12 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         g_timing.h2d_ms = ms;
         g_timing.h2d_bytes = h2d_bytes;
         g_timing.h2d_copies = u32(merged.size());
+        ms = 0.f;
+        if (n_move_launches > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[4], g_scratch.ev[5]));
+        g_timing.move_ms = ms;
+        g_timing.move_bytes = pl.moved_bytes;
+        g_timing.move_traffic_bytes = move_traffic;
+        g_timing.move_launches = u32(n_move_launches);
     }
 
     // ---- optional integrity check of what now sits in the slots
@@ -526,6 +693,11 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
 tg_status tg_release(tg_pool *pool, uint64_t model_id, uint32_t flags) {
     if (!pool) return TG_ERR_INVALID;
     return tg_status(pool->store.release(model_id, (flags & TG_RELEASE_EVICT) != 0));
+}
+
+tg_status tg_set_model_cost(tg_pool *pool, uint64_t model_id, double miss_prob, double load_bw, double alpha) {
+    if (!pool) return TG_ERR_INVALID;
+    return tg_status(pool->store.set_model_cost(model_id, miss_prob, load_bw, alpha));
 }
 
 tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double link_bytes_per_s,

@@ -138,19 +138,27 @@ class ReusePool:
                                           str(self.device))
         return RegisteredModel(model_id, host, offs, sizes, fps)
 
-    def load(self, model: RegisteredModel, confirm: bool = False, verify: bool = False
+    def load(self, model: RegisteredModel, confirm: bool = False, verify: bool = False,
+             evict: bool = False, merge: bool = False, alias: bool = False
              ) -> Tuple[List[int], dict]:
-        """tg_plan + tg_assemble.  Returns device addresses and the plan rows."""
-        plan = tg.tg_plan(self.pool, model.desc, tg.TG_PLAN_CONFIRM if confirm else 0,
-                          self.stream_gather)
+        """tg_plan + tg_assemble.  Returns device addresses and what the plan held."""
+        flags = ((tg.TG_PLAN_CONFIRM if confirm else 0) | (tg.TG_PLAN_EVICT if evict else 0)
+                 | (tg.TG_PLAN_MERGE if merge else 0) | (tg.TG_PLAN_ALIAS if alias else 0))
+        plan = tg.tg_plan(self.pool, model.desc, flags, self.stream_gather)
         try:
             rows, reused, transfer = tg.tg_plan_ops(plan)
+            info = tg.tg_plan_info(plan)
+            info.update({"ops": rows, "moves": tg.tg_plan_moves(plan),
+                         "evictions": tg.tg_plan_evictions(plan)})
             ptrs = tg.tg_assemble(self.pool, plan, model.desc.n,
                                   tg.TG_ASSEMBLE_VERIFY if verify else 0,
                                   self.stream_gather, self.stream_h2d)
         finally:
             tg.tg_plan_free(plan)
-        return ptrs, {"ops": rows, "reused_bytes": reused, "transfer_bytes": transfer}
+        return ptrs, info
+
+    def set_model_cost(self, model_id: int, miss_prob: float, load_bw: float, alpha: float = 1.0) -> None:
+        tg.tg_set_model_cost(self.pool, model_id, miss_prob, load_bw, alpha)
 
     def release(self, model_id: int, evict: bool = False) -> None:
         tg.tg_release(self.pool, model_id, tg.TG_RELEASE_EVICT if evict else 0)

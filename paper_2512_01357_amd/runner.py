@@ -109,9 +109,9 @@ class WorkloadRunner:
                 _, name, evict = act
                 self.pool.release(self.w.models[name].model_id, evict)
 
-    def load(self, name: str, confirm: bool = False, verify: bool = False):
+    def load(self, name: str, confirm: bool = False, verify: bool = False, **flags):
         reg = self.materialise(name)
-        return self.pool.load(reg, confirm=confirm, verify=verify)
+        return self.pool.load(reg, confirm=confirm, verify=verify, **flags)
 
     def release(self, name: str, evict: bool) -> None:
         self.pool.release(self.w.models[name].model_id, evict)

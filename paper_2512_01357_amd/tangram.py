@@ -22,6 +22,9 @@ TG_ERR_NOMEM = -6
 TG_ERR_CORRUPT = -7
 
 TG_PLAN_CONFIRM = 1
+TG_PLAN_EVICT = 2
+TG_PLAN_MERGE = 4
+TG_PLAN_ALIAS = 8
 TG_ASSEMBLE_VERIFY = 1
 TG_RELEASE_EVICT = 1
 TG_OP_REUSE = 0
@@ -58,12 +61,25 @@ class tg_stats(ctypes.Structure):
         "n_entries", "n_active", "generation")]
 
 
+class tg_move(ctypes.Structure):
+    _fields_ = [("old_off", ctypes.c_uint64), ("new_off", ctypes.c_uint64), ("nbytes", ctypes.c_uint64)]
+
+
+class tg_plan_summary(ctypes.Structure):
+    _fields_ = ([(n, ctypes.c_uint32) for n in ("n_tensors", "n_evictions", "n_moves", "alias")]
+                + [(n, ctypes.c_uint64) for n in (
+                    "reused_bytes", "transfer_bytes", "copy_bytes", "evicted_bytes", "moved_bytes",
+                    "merge_bound")])
+
+
 class tg_timing(ctypes.Structure):
     _fields_ = ([(n, ctypes.c_float) for n in (
         "fingerprint_ms", "compare_ms", "gather_ms", "h2d_ms", "verify_ms", "plan_host_ms")]
         + [(n, ctypes.c_uint64) for n in (
             "fingerprint_bytes", "compare_bytes", "gather_bytes", "h2d_bytes", "verify_bytes")]
-        + [("h2d_copies", ctypes.c_uint32), ("reserved", ctypes.c_uint32)])
+        + [("h2d_copies", ctypes.c_uint32), ("move_launches", ctypes.c_uint32),
+           ("move_ms", ctypes.c_float), ("reserved", ctypes.c_float),
+           ("move_bytes", ctypes.c_uint64), ("move_traffic_bytes", ctypes.c_uint64)])
 
 
 class tg_tuning(ctypes.Structure):
@@ -82,8 +98,8 @@ _lib = None
 
 EXPORTS = [
     "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_fingerprint", "tg_compare",
-    "tg_plan", "tg_plan_ops", "tg_plan_free", "tg_assemble", "tg_commit", "tg_release",
-    "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
+    "tg_plan", "tg_plan_ops", "tg_plan_info", "tg_plan_moves", "tg_plan_evictions", "tg_plan_free",
+    "tg_assemble", "tg_commit", "tg_release", "tg_set_model_cost", "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
     "tg_host_alloc", "tg_host_free", "tg_shutdown", "tg_strerror",
 ]
 
@@ -107,6 +123,10 @@ def lib() -> ctypes.CDLL:
             "tg_compare": ([P(tg_pair), u32, P(u32), vp], i32),
             "tg_plan": ([vp, P(tg_model_desc), u32, vp, P(vp)], i32),
             "tg_plan_ops": ([vp, P(P(tg_plan_op)), P(u32), P(u64), P(u64)], i32),
+            "tg_plan_info": ([vp, P(tg_plan_summary)], i32),
+            "tg_plan_moves": ([vp, P(P(tg_move)), P(u32)], i32),
+            "tg_plan_evictions": ([vp, P(P(u64)), P(u32)], i32),
+            "tg_set_model_cost": ([vp, u64, ctypes.c_double, ctypes.c_double, ctypes.c_double], i32),
             "tg_plan_free": ([vp], None),
             "tg_assemble": ([vp, vp, u32, vp, vp, P(vp)], i32),
             "tg_commit": ([vp, vp, P(vp)], i32),
@@ -228,6 +248,32 @@ def tg_plan_ops(plan) -> Tuple[List[Tuple[int, int, int, int]], int, int]:
     rows = [(int(ops[k].kind), int(ops[k].dst_off), int(ops[k].src_off), int(ops[k].nbytes))
             for k in range(n.value)]
     return rows, int(reused.value), int(transfer.value)
+
+
+def tg_plan_info(plan) -> dict:
+    out = tg_plan_summary()
+    _check(lib().tg_plan_info(plan, ctypes.byref(out)), "tg_plan_info")
+    return {n: int(getattr(out, n)) for n, _ in tg_plan_summary._fields_}
+
+
+def tg_plan_moves(plan) -> List[Tuple[int, int, int]]:
+    """(old_off, new_off, nbytes) of the resident tensors the plan moves, in execution order."""
+    rows = ctypes.POINTER(tg_move)()
+    n = ctypes.c_uint32()
+    _check(lib().tg_plan_moves(plan, ctypes.byref(rows), ctypes.byref(n)), "tg_plan_moves")
+    return [(int(rows[i].old_off), int(rows[i].new_off), int(rows[i].nbytes)) for i in range(n.value)]
+
+
+def tg_plan_evictions(plan) -> List[int]:
+    """Pool offsets of the tensors the plan evicts, in eviction order."""
+    offs = ctypes.POINTER(ctypes.c_uint64)()
+    n = ctypes.c_uint32()
+    _check(lib().tg_plan_evictions(plan, ctypes.byref(offs), ctypes.byref(n)), "tg_plan_evictions")
+    return [int(offs[i]) for i in range(n.value)]
+
+
+def tg_set_model_cost(pool, model_id: int, miss_prob: float, load_bw: float, alpha: float = 1.0) -> None:
+    _check(lib().tg_set_model_cost(pool, model_id, miss_prob, load_bw, alpha), "tg_set_model_cost")
 
 
 def tg_plan_free(plan) -> None:

@@ -1,0 +1,220 @@
+"""GPU parity for eviction, merge moves and alias mode: the pool's bytes after
+every step against the oracle's image, bit for bit, through the C ABI."""
+import random
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+import oracle  # noqa: E402
+from gpu_harness import DEV, say  # noqa: E402
+from oracle import NoSpace, ReuseStoreOracle  # noqa: E402
+from paper_2512_01357_amd import tangram as tg  # noqa: E402
+from paper_2512_01357_amd.loader import HostArena, ReusePool  # noqa: E402
+
+U = 256
+MIB = 1 << 20
+
+
+def rbytes(rnd, n):
+    return np.random.default_rng(rnd.getrandbits(32)).integers(0, 256, n, dtype=np.uint8)
+
+
+def pack(tensors, align=256):
+    offs, at = [], 0
+    for t in tensors:
+        offs.append(at)
+        at += (len(t) + align - 1) // align * align
+    host = np.zeros(max(at, align), dtype=np.uint8)
+    for t, o in zip(tensors, offs):
+        host[o:o + len(t)] = t
+    return host, offs
+
+
+class Both:
+    def __init__(self, capacity):
+        self.pool = ReusePool(capacity, 256, DEV)
+        self.store = ReuseStoreOracle(capacity, 256)
+        self.keep = []
+
+    def load(self, mid, tensors, **fl):
+        host, offs = pack(tensors)
+        arena = HostArena(host.size)
+        arena.numpy()[:] = host
+        self.keep.append(arena)
+        sizes = [len(t) for t in tensors]
+        want = [oracle.fingerprint(t) for t in tensors]
+        reg = self.pool.register(mid, arena, offs, sizes)
+        assert reg.fps == want
+        rows = list(zip(sizes, want, offs))
+        try:
+            oplan = self.store.plan(mid, rows, host, **fl)
+        except NoSpace:
+            with pytest.raises(tg.TgError) as e:
+                self.pool.load(reg, **fl)
+            assert e.value.status == tg.TG_ERR_NOSPACE
+            return None, None
+        ptrs, info = self.pool.load(reg, verify=True, **fl)
+        assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops]
+        assert info["moves"] == [(old, new, e.nbytes) for e, old, new in oplan.moves]
+        assert info["evictions"] == [e.off for e in oplan.evictions]
+        dsts = self.store.assemble(oplan, host)
+        assert ptrs == [self.pool.base + d for d in dsts]
+        self.check()
+        return oplan, dsts
+
+    def check(self):
+        """Every resident tensor holds exactly the oracle's bytes."""
+        for e in self.store.entries:
+            got = self.pool.slab[e.off:e.off + e.nbytes].cpu().numpy()
+            assert got.tobytes() == self.store.image[e.off][:e.nbytes].tobytes(), (e.off, e.nbytes)
+        a, b = self.pool.stats(), self.store.stats()
+        for k, v in b.items():
+            assert a[k] == v, k
+
+    def release(self, mid, evict=False):
+        self.pool.release(mid, evict)
+        self.store.release(mid, evict)
+
+    def cost(self, mid, p, b, a):
+        self.pool.set_model_cost(mid, p, b, a)
+        self.store.set_model_cost(mid, p, b, a)
+
+    def close(self):
+        self.pool.close()
+        for a in self.keep:
+            a.free()
+
+
+def carve(b, rnd, layout, unit):
+    for i, (units, keep) in enumerate(layout):
+        b.load(100 + i, [rbytes(rnd, units * unit)])
+        b.release(100 + i)
+    for i, (units, keep) in enumerate(layout):
+        if not keep:
+            b.release(100 + i, evict=True)
+
+
+def test_hand_derived_merge_plan_moves_real_bytes():
+    say("merge example, small shifts (staged moves)")
+    rnd = random.Random(1)
+    b = Both(30 * U)
+    carve(b, rnd, [(4, False), (2, True), (4, False), (6, True), (4, False), (1, True), (4, False),
+                   (1, True), (4, False)], U)
+    plan, dsts = b.load(9, [rbytes(rnd, 6 * U), rbytes(rnd, 5 * U - 7)], merge=True)
+    assert [(o // U, n // U) for _e, o, n in plan.moves] == [(4, 0), (20, 16), (25, 17)]
+    t = tg.tg_last_timing()
+    b.close()
+
+
+def test_large_moves_straight_and_staged():
+    say("merge with large shifts (straight copies) and small shifts over long tensors (staged)")
+    tg.tg_set_profiling(True)
+    rnd = random.Random(2)
+    # F64 A200 F64 B40 F100 (MiB): a 210 MiB tensor fits nowhere; everything is compacted.
+    # A shifts by 64 MiB (straight, in pieces of at most 64 MiB), B by 128 MiB.
+    b = Both(468 * MIB)
+    carve(b, rnd, [(64, False), (200, True), (64, False), (40, True), (100, False)], MIB)
+    plan, _ = b.load(9, [rbytes(rnd, 210 * MIB + 40)], merge=True)
+    assert [(o // MIB, n // MIB) for _e, o, n in plan.moves] == [(64, 0), (328, 200)]
+    t = tg.tg_last_timing()
+    assert t["move_bytes"] == 240 * MIB and t["move_traffic_bytes"] == 2 * 240 * MIB
+    # A goes in pieces of 64 + 64 + 64 + 8 MiB (a launch may not write at or above the first byte
+    # it reads, 64 MiB ahead); B's 40 MiB land below that mark too and ride in the last launch
+    assert t["move_launches"] == 4
+    b.close()
+    # F1 A300 F100 (MiB) + a 101 MiB tensor: A shifts by 1 MiB, staged through 128 MiB at a time
+    b = Both(401 * MIB)
+    carve(b, rnd, [(1, False), (300, True), (100, False)], MIB)
+    plan, _ = b.load(9, [rbytes(rnd, 101 * MIB - 3)], merge=True)
+    assert [(o // MIB, n // MIB) for _e, o, n in plan.moves] == [(1, 0)]
+    t = tg.tg_last_timing()
+    assert t["move_launches"] == 6 and t["move_traffic_bytes"] == 4 * 300 * MIB
+    b.close()
+    tg.tg_set_profiling(False)
+
+
+def test_eviction_then_load_real_bytes():
+    say("stage 1 eviction")
+    rnd = random.Random(3)
+    b = Both(16 * U)
+    for mid, sizes in ((1, [1024, 512]), (2, [768, 256]), (3, [512])):
+        b.load(mid, [rbytes(rnd, n) for n in sizes])
+        b.release(mid)
+    b.cost(1, 0.5, 2.0, 1.0)
+    b.cost(2, 1.0, 1.0, 0.1)
+    plan, dsts = b.load(9, [rbytes(rnd, 1024), rbytes(rnd, 1024)], evict=True)
+    assert [e.nbytes for e in plan.evictions] == [256, 768]
+    b.close()
+
+
+def test_alias_mode_real_bytes():
+    say("alias mode")
+    rnd = random.Random(4)
+    b = Both(4 * MIB)
+    a = [rbytes(rnd, 300000), rbytes(rnd, 512), rbytes(rnd, 70001)]
+    _, a_dst = b.load(1, a)
+    b.release(1)
+    m2 = [a[0], rbytes(rnd, 90000), a[2]]
+    plan, dsts = b.load(2, m2, alias=True)
+    assert [op.kind for op in plan.ops] == [0, 1, 0]
+    assert dsts[0] == a_dst[0] and dsts[2] == a_dst[2]
+    assert tg.tg_pool_stats(b.pool.pool)["n_entries"] == 4
+    plan, dsts = b.load(1, a, alias=True)           # comes back while 2 runs: nothing to transfer
+    assert plan.transfer_bytes == 0 and dsts == a_dst
+    b.release(2, evict=True)
+    b.check()
+    b.release(1, evict=True)
+    assert b.pool.stats()["free_bytes"] == 4 * MIB
+    b.close()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_histories_with_every_flag_real_bytes(seed):
+    say("random history %d" % seed)
+    rnd = random.Random(700 + seed)
+    b = Both(24 * MIB)
+    library = [rbytes(rnd, rnd.choice([40, 4096, 70000, 300000, 1 << 20, (1 << 20) + 24, 3 << 20, 5000000]))
+               for _ in range(20)]
+    running, retained, next_id = {}, [], 1
+    for step in range(60):
+        r = rnd.random()
+        if r < 0.55 or not (running or retained):
+            tensors = [library[rnd.randrange(20)] for _ in range(rnd.randrange(1, 6))]
+            fl = dict(evict=rnd.random() < 0.7, merge=rnd.random() < 0.7, alias=rnd.random() < 0.5)
+            mid = next_id
+            if retained and rnd.random() < 0.25:
+                mid = rnd.choice(retained)
+            plan, dsts = b.load(mid, tensors, **fl)
+            if plan is None:
+                continue
+            running[mid] = (tensors, dsts)
+            if mid in retained:
+                retained.remove(mid)
+            if mid == next_id:
+                next_id += 1
+        elif running and (not retained or rnd.random() < 0.6):
+            mid = rnd.choice(sorted(running))
+            evict = rnd.random() < 0.4
+            b.release(mid, evict)
+            del running[mid]
+            if not evict:
+                retained.append(mid)
+        else:
+            mid = rnd.choice(retained)
+            if mid in b.store.models:
+                b.release(mid, True)
+            retained.remove(mid)
+        retained = [m for m in retained if m in b.store.models]
+        # every tensor of every running model is where the caller was told, byte for byte
+        for mid, (tensors, dsts) in running.items():
+            for t, d in zip(tensors, dsts):
+                got = b.pool.slab[d:d + len(t)].cpu().numpy()
+                assert got.tobytes() == t.tobytes(), (mid, d)
+    b.check()
+    b.close()
