@@ -143,7 +143,10 @@ def main():
     ap.add_argument("--steps", type=int, default=9)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b",
-                    help="tiny | gpt1b | llama7b | neox20b | llama70b-0 | llama70b-50 | llama70b-90")
+                    help="tiny | gpt1b | llama7b | neox20b | llama70b-0 | llama70b-50 | llama70b-90 | "
+                         "merge | merge-listing | merge-notail | merge-small")
+    ap.add_argument("--alias", action="store_true",
+                    help="plan with TG_PLAN_ALIAS: resident tensors are used where they lie")
     ap.add_argument("--no-verify", action="store_true", help="skip the fingerprint of assembled slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pool-gb", type=float, default=0.0, help="override pool size (70B)")
@@ -172,7 +175,9 @@ def main():
         w = synth.workload_llama70b(frac, pool)
     else:
         w = synth.WORKLOADS[args.workload]()
-    log("workload %s: pool %.1f GB, loads %s" % (w.name, w.pool_bytes / 1e9, w.loads))
+    if args.alias:
+        w.load_flags = dict(w.load_flags, alias=True)
+    log("workload %s: pool %.1f GB, loads %s, flags %s" % (w.name, w.pool_bytes / 1e9, w.loads, w.load_flags))
 
     link_peak = measure_link_peak(torch)
     log("host link peak (2 GiB pinned->device): %.2f GB/s" % link_peak)
@@ -200,6 +205,19 @@ def main():
 
     def step(i):
         """One whole load of one model (+ release).  Returns its records."""
+        if w.rebuild_each_step:
+            # the load moves or evicts residents: only the load is timed, then the
+            # pool is rebuilt from scratch
+            name = names[i % len(names)]
+            reg = r.materialise(name)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ptrs, info = r.load(name, verify=verify)
+            torch.cuda.synchronize()
+            timed = time.perf_counter() - t0
+            t = tg.tg_last_timing()
+            r.reset_pool()
+            return [(name, info, t, reg.nbytes)], timed
         if not w.streamed:
             name = names[i % len(names)]
             ptrs, info = r.load(name, verify=verify)
@@ -239,7 +257,7 @@ def main():
         if timed is not None:
             timed_total += timed
     torch.cuda.synchronize()
-    elapsed = timed_total if w.streamed else time.perf_counter() - t_begin
+    elapsed = timed_total if (w.streamed or w.rebuild_each_step) else time.perf_counter() - t_begin
     st1 = r.pool.stats()
     if any(st1[k] != st0[k] for k in st0 if k != "generation"):
         raise RuntimeError("pool did not return to its starting state: %s vs %s" % (st1, st0))
@@ -270,7 +288,7 @@ def main():
                    "algorithmic_bytes_per_launch": int(2 * sum(rec[2]["gather_bytes"] for rec in recs) / len(recs)),
                    "traffic": None},
     }
-    if verify and w.name in PMC_TRAFFIC_BYTES:
+    if verify and w.name in PMC_TRAFFIC_BYTES and not any(w.load_flags.values()):
         for k, v in PMC_TRAFFIC_BYTES[w.name].items():
             kernels[k]["traffic"] = v
     dominant = max(kernels, key=lambda k: kernels[k]["avg_ms"])
@@ -287,6 +305,7 @@ def main():
                    "pool_bytes": w.pool_bytes,
                    "reused_fraction": round(sum(rec[1]["reused_bytes"] for rec in recs) / total_bytes, 4),
                    "verify_fingerprint": verify,
+                   "plan_flags": sorted(k for k, v in w.load_flags.items() if v),
                    "model_cache": ("streamed in %d parts (pinned host memory is capped below the model size); "
                                    "only the loads are timed" % len(names)) if w.streamed else "whole model pinned"},
         "fingerprint_GBps": round(fp_gbps, 1),
@@ -301,6 +320,40 @@ def main():
                                     * 1e3 / args.steps, 3),
     }
 
+    # the fingerprint kernel on its own: launches back to back over one loaded model's
+    # slots (in a step it runs once, right after a long link-bound phase during which
+    # the memory clocks have dropped, which costs it up to a fifth of its bandwidth)
+    if not w.rebuild_each_step:
+        name = names[-1]
+        reg = r.materialise(name)
+        ptrs, _info = r.load(name)
+        spans = list(zip(ptrs, reg.sizes))
+        ms = []
+        for _ in range(6):
+            got = tg.tg_fingerprint(spans, r.pool.stream_gather)
+            ms.append(tg.tg_last_timing()["fingerprint_ms"])
+        if got != reg.fps:
+            raise RuntimeError("fingerprints of the loaded model differ from its descriptors")
+        r.release(name, True)
+        best = min(ms[1:])
+        out["fingerprint_back_to_back"] = {
+            "GBps": round(reg.nbytes / (best * 1e-3) / 1e9, 1), "frac": round(reg.nbytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "ms": round(best, 4), "bytes": reg.nbytes, "launches": len(ms) - 1}
+
+    if any(rec[1].get("n_moves") or rec[1].get("n_evictions") for rec in recs):
+        mv_ms = sum(rec[2]["move_ms"] for rec in recs)
+        mv_traffic = sum(rec[2]["move_traffic_bytes"] for rec in recs)
+        out["merge"] = {
+            "moved_bytes_per_load": int(sum(rec[1]["moved_bytes"] for rec in recs) / len(recs)),
+            "merge_bound_per_load": int(sum(rec[1]["merge_bound"] for rec in recs) / len(recs)),
+            "merge_all_bytes": int(st0["capacity"] - st0["free_bytes"]),
+            "evicted_bytes_per_load": int(sum(rec[1]["evicted_bytes"] for rec in recs) / len(recs)),
+            "move_ms": round(mv_ms / len(recs), 4),
+            "move_launches": recs[0][2]["move_launches"],
+            "move_traffic_GBps": round(mv_traffic / (mv_ms * 1e-3) / 1e9, 1) if mv_ms > 0 else 0.0,
+            "move_traffic_frac_of_hbm_peak": round(mv_traffic / (mv_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if mv_ms > 0 else 0.0,
+            "moved_GBps": round(sum(rec[2]["move_bytes"] for rec in recs) / (mv_ms * 1e-3) / 1e9, 1) if mv_ms > 0 else 0.0,
+        }
     if not args.no_cpu_baseline:
         if not baseline:
             log("timing the CPU oracle on a bounded sample ...")

@@ -56,6 +56,7 @@ typedef int32_t tg_status;
 #define TG_PLAN_EVICT     2u   /* Stage 1: evict retained tensors by ascending cost when free bytes are short */
 #define TG_PLAN_MERGE     4u   /* Stage 2: when best fit fails, pack by partitions and merge free regions */
 #define TG_PLAN_ALIAS     8u   /* a hit is used where it lies (no copy, no new slot) */
+#define TG_PLAN_PACK_TEXT 16u  /* Stage 2 packing test as the text words it (see tg_plan) */
 /* tg_assemble flags */
 #define TG_ASSEMBLE_VERIFY 1u  /* fingerprint every assembled slot and compare with the descriptor */
 /* tg_release flags */
@@ -240,7 +241,12 @@ tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, vo
  *           takes its tensors by best fit if it can, else its resident tensors
  *           are slid to its low end (tg_plan_moves) and the tensors placed in
  *           the merged free tail.  Tensors in use by a running model never
- *           move; they split the pool beforehand.
+ *           move; they split the pool beforehand.  The packing test is the
+ *           listing's (a tensor must be smaller than the smaller bin's
+ *           remaining room; it goes to the bin with more room); the paper's
+ *           text words it differently (the tensor only has to fit the bin with
+ *           more room), which TG_PLAN_PACK_TEXT selects and which splits far
+ *           more often.
  *
  * The pool is not modified.  *out receives a plan bound to the pool's current
  * generation.  TG_ERR_INVALID: null arguments, unknown flag bits, n_tensors ==

@@ -30,7 +30,8 @@ ones the product documents):
     points are tried in order of descending gain (ties: lower offset); the
     packing test is the listing's: a tensor must be smaller than the smaller
     bin's remaining capacity, and goes to the bin with more room (ties: the
-    first); regions in use by a running model cannot move and split the pool
+    first) -- the text words the test differently (the tensor only has to fit
+    the bin with more room), which is available as ``pack_text``; regions in use by a running model cannot move and split the pool
     before the algorithm starts (there a tensor goes to the side with more
     room and only has to fit it); a final subspace first tries plain best fit
     inside itself and is compacted towards its low end only if that fails;
@@ -205,8 +206,18 @@ def free_bytes_of(regions: List[List], sub: Optional[Tuple[int, int]]) -> int:
     return sum(r[1] for r in regions[sub[0]:sub[1]] if r[2])
 
 
+def try_packing_text(sizes: Sequence[int], tensors: List[int], c1: int, c2: int
+                     ) -> Tuple[List[int], List[int]]:
+    """TryPacking as the text of Section 3.2 words it (the listing and the text
+    differ): a tensor goes to the bin with the largest remaining space and the
+    attempt fails only if it does not fit into that bin."""
+    parts = split_at_wall(sizes, tensors, c1, c2)
+    return ([], []) if parts is None else parts
+
+
 def partitioned_gain_packing(regions: List[List], sizes: Sequence[int], order: List[int],
-                             movable) -> Optional[Tuple[List[Tuple[Tuple[int, int], List[int]]], int]]:
+                             movable, pack=try_packing
+                             ) -> Optional[Tuple[List[Tuple[Tuple[int, int], List[int]]], int]]:
     """Algorithm 1.  `regions` is the Region List, `order` the new tensors in
     descending size, `movable(region)` tells whether an allocated region may
     move.  Returns (allocation set A as ((lo, hi), tensor subset) pairs in
@@ -249,7 +260,7 @@ def partitioned_gain_packing(regions: List[List], sizes: Sequence[int], order: L
             split = False
             for p in points:
                 p1, p2 = trim(regions, sub[0], p), trim(regions, p + 1, sub[1])
-                t1, t2 = try_packing(sizes, tensors, free_bytes_of(regions, p1), free_bytes_of(regions, p2))
+                t1, t2 = pack(sizes, tensors, free_bytes_of(regions, p1), free_bytes_of(regions, p2))
                 if t1 or t2:
                     if p1 is not None:
                         nxt.append((p1, t1))
@@ -331,7 +342,7 @@ class ReuseStoreOracle:
     # ------------------------------------------------------------------- plan
     def plan(self, model_id: int, tensors: Sequence[Tuple[int, int, int]],
              host: Optional[np.ndarray] = None, confirm: bool = False, evict: bool = False,
-             merge: bool = False, alias: bool = False) -> OraclePlan:
+             merge: bool = False, alias: bool = False, pack_text: bool = False) -> OraclePlan:
         """``tensors[k] = (nbytes, fp, host_off)``.  Pure: the store is not
         modified; the result records everything the commit will install."""
         if model_id in self.models and self.models[model_id]["active"]:
@@ -393,7 +404,8 @@ class ReuseStoreOracle:
             # ---- Stage 2: Partitioned-Gain Packing (Algorithm 1)
             dsts = {}
             res = partitioned_gain_packing(regions, sizes, order,
-                                           lambda r: r[3] is not None and r[3].active_refs == 0)
+                                           lambda r: r[3] is not None and r[3].active_refs == 0,
+                                           try_packing_text if pack_text else try_packing)
             if res is None:
                 raise NoSpace("running models' tensors separate the free space")
             final, merge_bound = res

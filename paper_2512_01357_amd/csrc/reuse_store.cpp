@@ -145,7 +145,7 @@ bool split_at_wall(const std::vector<uint64_t> &sizes, const std::vector<uint32_
 // Returns false when immovable regions keep the tensors from being split.
 bool partitioned_gain_packing(const std::vector<Flat> &regs, const std::vector<uint64_t> &sizes,
                               const std::vector<uint32_t> &order, const std::vector<char> &movable,
-                              std::vector<Subspace> &final_set, uint64_t &merge_cost) {
+                              bool pack_text, std::vector<Subspace> &final_set, uint64_t &merge_cost) {
     final_set.clear();
     Range whole = trim(regs, 0, regs.size());
     if (!whole.ok) return false;
@@ -193,7 +193,14 @@ bool partitioned_gain_packing(const std::vector<Flat> &regs, const std::vector<u
             bool split = false;
             for (size_t p : points) {
                 const Range p1 = trim(regs, s.lo, p), p2 = trim(regs, p + 1, s.hi);
-                try_packing(sizes, s.tensors, free_bytes_of(regs, p1), free_bytes_of(regs, p2), t1, t2);
+                // the listing's test, or the one the text words (a tensor only has to fit
+                // the bin with more room)
+                if (!pack_text) {
+                    try_packing(sizes, s.tensors, free_bytes_of(regs, p1), free_bytes_of(regs, p2), t1, t2);
+                } else if (!split_at_wall(sizes, s.tensors, free_bytes_of(regs, p1), free_bytes_of(regs, p2), t1, t2)) {
+                    t1.clear();
+                    t2.clear();
+                }
                 if (!t1.empty() || !t2.empty()) {
                     if (p1.ok) next.push_back(Subspace{p1.lo, p1.hi, t1});
                     if (p2.ok) next.push_back(Subspace{p2.lo, p2.hi, t2});
@@ -344,7 +351,8 @@ Status ReuseStore::plan(const std::vector<TensorIn> &tensors, const std::vector<
             for (size_t i = 0; i < regs.size(); ++i)
                 if (!regs[i].free) movable[i] = entries_.at(regs[i].tag).active_refs == 0;
             std::vector<Subspace> final_set;
-            if (!partitioned_gain_packing(regs, sizes, order, movable, final_set, plan.merge_bound))
+            if (!partitioned_gain_packing(regs, sizes, order, movable, (flags & PLAN_PACK_TEXT) != 0, final_set,
+                                          plan.merge_bound))
                 return ERR_NOSPACE;
             // realise the subspaces; the flat list is rebuilt piece by piece in address order
             std::vector<Flat> out;

@@ -21,7 +21,7 @@ enum Status : int32_t {
     ERR_NOMEM = -6, ERR_CORRUPT = -7
 };
 
-enum PlanFlags : uint32_t { PLAN_CONFIRM = 1, PLAN_EVICT = 2, PLAN_MERGE = 4, PLAN_ALIAS = 8 };
+enum PlanFlags : uint32_t { PLAN_CONFIRM = 1, PLAN_EVICT = 2, PLAN_MERGE = 4, PLAN_ALIAS = 8, PLAN_PACK_TEXT = 16 };
 
 // Region tags: 0 = none, otherwise an entry id; ids at or above kNewTag mark
 // the slot of tensor (tag - kNewTag) of a plan that has not been committed.

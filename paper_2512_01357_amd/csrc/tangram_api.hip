@@ -372,7 +372,8 @@ tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, vo
 tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
                   tg_load_plan **out) {
     if (!pool || !out) return TG_ERR_INVALID;
-    if (flags & ~(TG_PLAN_CONFIRM | TG_PLAN_EVICT | TG_PLAN_MERGE | TG_PLAN_ALIAS)) return TG_ERR_INVALID;
+    if (flags & ~(TG_PLAN_CONFIRM | TG_PLAN_EVICT | TG_PLAN_MERGE | TG_PLAN_ALIAS | TG_PLAN_PACK_TEXT))
+        return TG_ERR_INVALID;
     const auto t0 = std::chrono::steady_clock::now();
     std::vector<tg::TensorIn> tensors;
     tg_status rc = check_model(model, tensors);

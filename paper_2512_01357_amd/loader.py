@@ -139,11 +139,12 @@ class ReusePool:
         return RegisteredModel(model_id, host, offs, sizes, fps)
 
     def load(self, model: RegisteredModel, confirm: bool = False, verify: bool = False,
-             evict: bool = False, merge: bool = False, alias: bool = False
-             ) -> Tuple[List[int], dict]:
+             evict: bool = False, merge: bool = False, alias: bool = False,
+             pack_text: bool = False) -> Tuple[List[int], dict]:
         """tg_plan + tg_assemble.  Returns device addresses and what the plan held."""
         flags = ((tg.TG_PLAN_CONFIRM if confirm else 0) | (tg.TG_PLAN_EVICT if evict else 0)
-                 | (tg.TG_PLAN_MERGE if merge else 0) | (tg.TG_PLAN_ALIAS if alias else 0))
+                 | (tg.TG_PLAN_MERGE if merge else 0) | (tg.TG_PLAN_ALIAS if alias else 0)
+                 | (tg.TG_PLAN_PACK_TEXT if pack_text else 0))
         plan = tg.tg_plan(self.pool, model.desc, flags, self.stream_gather)
         try:
             rows, reused, transfer = tg.tg_plan_ops(plan)

@@ -110,8 +110,21 @@ class WorkloadRunner:
                 self.pool.release(self.w.models[name].model_id, evict)
 
     def load(self, name: str, confirm: bool = False, verify: bool = False, **flags):
+        """Loads a model; plan flags default to the workload's for its measured loads."""
         reg = self.materialise(name)
+        if not flags and name in self.w.loads:
+            flags = dict(self.w.load_flags)
         return self.pool.load(reg, confirm=confirm, verify=verify, **flags)
+
+    def reset_pool(self) -> None:
+        """Evict everything and replay the setup (for workloads whose measured
+        load moves or evicts residents)."""
+        for spec in self.w.models.values():
+            try:
+                self.pool.release(spec.model_id, True)
+            except Exception:
+                pass
+        self.run_setup()
 
     def release(self, name: str, evict: bool) -> None:
         self.pool.release(self.w.models[name].model_id, evict)

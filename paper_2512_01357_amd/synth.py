@@ -71,6 +71,11 @@ class Workload:
     # True when the measured model is cut into parts that pass through the
     # Model Cache one after the other (all parts together are one load)
     streamed: bool = False
+    # plan flags for the measured loads: any of "evict", "merge", "alias"
+    load_flags: Dict[str, bool] = field(default_factory=dict)
+    # True when a measured load changes the pool beyond what releasing the model
+    # undoes (it moved or evicted residents): the setup is replayed before each step
+    rebuild_each_step: bool = False
 
 
 def seed_for(cfg: int, model: int, k: int) -> int:
@@ -309,11 +314,46 @@ def workload_llama70b(reuse: float, pool_bytes: int, part_bytes: int = 48 * 10**
     return w
 
 
+def workload_merge(hole_mib: int = 320, residents: int = 16, resident_mib: int = 1024,
+                   new_tensors: int = 4, new_mib: int = 1000, tail_mib: int = 3072,
+                   pack_text: bool = True) -> Workload:
+    """`residents` retained tensors of resident_mib MiB, each followed by a hole
+    of hole_mib MiB, then a free tail of tail_mib MiB.  The incoming model's
+    tensors (new_mib MiB each) fit the free bytes but not all of them fit the
+    tail and none fits a hole, so best fit fails and Stage 2 has to merge free
+    regions by moving residents."""
+    mib = 1 << 20
+    models: Dict[str, ModelSpec] = {}
+    setup: List[tuple] = []
+    for i in range(residents):
+        k = ModelSpec("K%d" % i, 10 + i, [TensorSpec("k%d" % i, (resident_mib * mib // 2,), "normal",
+                                                     seed_for(6, i, 0))])
+        h = ModelSpec("H%d" % i, 500 + i, [TensorSpec("h%d" % i, (hole_mib * mib // 2,), "normal",
+                                                      seed_for(6, 100 + i, 0))])
+        models[k.name], models[h.name] = k, h
+        setup += [("load", k.name), ("release", k.name, False), ("load", h.name), ("release", h.name, False)]
+    for i in range(residents):
+        setup.append(("release", "H%d" % i, True))
+    n = ModelSpec("N", 1000, [TensorSpec("n%d" % j, (new_mib * mib // 2 - 8 * j,), "normal", seed_for(6, 200, j))
+                              for j in range(new_tensors)])
+    models["N"] = n
+    pool = (residents * (resident_mib + hole_mib) + tail_mib) * mib
+    w = Workload("merge-holes-%dMiB" % hole_mib, pool, 256, models, setup, ["N"])
+    w.load_flags = {"merge": True, "pack_text": pack_text}
+    w.rebuild_each_step = True
+    return w
+
+
 WORKLOADS = {
     "tiny": workload_tiny,
     "gpt1b": workload_gpt1b,
     "llama7b": workload_llama7b,
     "neox20b": workload_neox20b,
+    "merge": workload_merge,
+    "merge-listing": lambda: workload_merge(pack_text=False),
+    "merge-notail": lambda: workload_merge(tail_mib=0),
+    "merge-small": lambda: workload_merge(hole_mib=16, residents=16, resident_mib=512, new_tensors=2,
+                                          new_mib=120, tail_mib=0),
 }
 
 

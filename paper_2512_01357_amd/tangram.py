@@ -25,6 +25,7 @@ TG_PLAN_CONFIRM = 1
 TG_PLAN_EVICT = 2
 TG_PLAN_MERGE = 4
 TG_PLAN_ALIAS = 8
+TG_PLAN_PACK_TEXT = 16
 TG_ASSEMBLE_VERIFY = 1
 TG_RELEASE_EVICT = 1
 TG_OP_REUSE = 0

@@ -186,7 +186,8 @@ def test_random_histories_with_every_flag_real_bytes(seed):
         r = rnd.random()
         if r < 0.55 or not (running or retained):
             tensors = [library[rnd.randrange(20)] for _ in range(rnd.randrange(1, 6))]
-            fl = dict(evict=rnd.random() < 0.7, merge=rnd.random() < 0.7, alias=rnd.random() < 0.5)
+            fl = dict(evict=rnd.random() < 0.7, merge=rnd.random() < 0.7, alias=rnd.random() < 0.5,
+                      pack_text=rnd.random() < 0.5)
             mid = next_id
             if retained and rnd.random() < 0.25:
                 mid = rnd.choice(retained)

@@ -16,9 +16,9 @@ FAKE_HOST = 1 << 41
 U = 256
 
 
-def flags_of(evict=False, merge=False, alias=False):
+def flags_of(evict=False, merge=False, alias=False, pack_text=False):
     return (tg.TG_PLAN_EVICT if evict else 0) | (tg.TG_PLAN_MERGE if merge else 0) | \
-        (tg.TG_PLAN_ALIAS if alias else 0)
+        (tg.TG_PLAN_ALIAS if alias else 0) | (tg.TG_PLAN_PACK_TEXT if pack_text else 0)
 
 
 def plan_both(pool, store, mid, tensors, host_bytes, **fl):
@@ -126,7 +126,7 @@ def test_hand_derived_eviction_and_merge_examples():
 def test_unknown_flag_bits_are_refused():
     pool = tg.tg_pool_create(FAKE_BASE, 4096, 256)
     with pytest.raises(tg.TgError) as e:
-        tg.tg_plan(pool, tg.ModelDesc(1, FAKE_HOST, 4096, [(512, 1, 0)]), 16)
+        tg.tg_plan(pool, tg.ModelDesc(1, FAKE_HOST, 4096, [(512, 1, 0)]), 32)
     assert e.value.status == tg.TG_ERR_INVALID
     tg.tg_pool_destroy(pool)
 
@@ -144,7 +144,8 @@ def history(seed):
         if r < 0.5 or not (running or retained):
             picks = [contents[rnd.randrange(30)] for _ in range(rnd.randrange(1, 8))]
             rows, hb = layout_rows([p[0] for p in picks], [p[1] for p in picks])
-            fl = dict(evict=rnd.random() < 0.7, merge=rnd.random() < 0.7, alias=rnd.random() < 0.5)
+            fl = dict(evict=rnd.random() < 0.7, merge=rnd.random() < 0.7, alias=rnd.random() < 0.5,
+                      pack_text=rnd.random() < 0.5)
             mid = next_id
             if retained and rnd.random() < 0.25:
                 mid = rnd.choice(retained)
@@ -203,7 +204,7 @@ def test_random_histories_with_every_flag_match_the_oracle(seed):
 
 def test_the_random_histories_exercise_every_stage():
     totals = [0, 0, 0]
-    for seed in range(16, 24):
+    for seed in range(16, 40):
         for i, v in enumerate(history(seed)):
             totals[i] += v
     assert all(t > 20 for t in totals), totals

@@ -17,7 +17,7 @@ import pytest
 
 import oracle
 from oracle import H2D, REUSE, NoSpace, ReuseStoreOracle
-from oracle.reuse_store import partitioned_gain_packing, try_packing
+from oracle.reuse_store import partitioned_gain_packing, try_packing, try_packing_text
 
 U = 256
 
@@ -166,6 +166,19 @@ def test_try_packing_follows_the_listing():
     assert try_packing(sizes, [4], 4, 9) == ([], [])        # not strictly smaller than the smaller bin
     assert try_packing(sizes, [0, 5], 8, 12) == ([5], [0])  # 6 -> bin 2, then 5 < min(8, 6) -> bin 1
     assert try_packing(sizes, [], 8, 8) == ([], [])
+
+
+def test_try_packing_as_the_text_words_it():
+    sizes = [6, 1, 3, 3, 4, 5]
+    assert try_packing_text(sizes, [2, 3], 4, 4) == ([2], [3])   # each fits the bin with more room
+    assert try_packing_text(sizes, [4], 4, 9) == ([], [4])
+    assert try_packing_text(sizes, [4], 4, 3) == ([4], [])       # exact fit is a fit
+    assert try_packing_text(sizes, [0, 5], 5, 5) == ([], [])     # 6 fits neither
+    # four equal tensors over two equal halves: the listing's test gives up at the
+    # fourth, the text's places two on each side
+    s4 = [1000] * 4
+    assert try_packing(s4, [0, 1, 2, 3], 2560, 2560) == ([], [])
+    assert try_packing_text(s4, [0, 1, 2, 3], 2560, 2560) == ([0, 2], [1, 3])
 
 
 def regions_of(units):
@@ -333,7 +346,8 @@ def test_random_histories_with_every_flag(seed):
         r = rnd.random()
         if r < 0.5 or not (running or retained):
             tensors = [library[rnd.randrange(24)] for _ in range(rnd.randrange(1, 7))]
-            flags = dict(evict=rnd.random() < 0.7, merge=rnd.random() < 0.7, alias=rnd.random() < 0.5)
+            flags = dict(evict=rnd.random() < 0.7, merge=rnd.random() < 0.7, alias=rnd.random() < 0.5,
+                         pack_text=rnd.random() < 0.5)
             mid = next_id
             if retained and rnd.random() < 0.2:
                 mid = rnd.choice(sorted(retained))
