@@ -7,6 +7,7 @@
 // Partitioned-Gain Packing, Algorithm 1) and Eq. 3.
 #pragma once
 
+#include <cstddef>
 #include <cstdint>
 #include <map>
 #include <set>

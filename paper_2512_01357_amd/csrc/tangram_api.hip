@@ -289,6 +289,40 @@ tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
     return TG_OK;
 }
 
+// Last check before anything is enqueued: every extent a kernel or the copy
+// engine will touch lies inside the pool (or the model's host image), and no
+// two destinations overlap.  A planner bug then comes back as an error code
+// instead of a stray write.
+tg_status validate_plan(const tg::Plan &pl, const tg::ReuseStore &store) {
+    const uint64_t cap = store.capacity();
+    std::vector<std::pair<uint64_t, uint64_t>> dst;        // [begin, end) of every write
+    for (size_t k = 0; k < pl.ops.size(); ++k) {
+        const tg::Op &op = pl.ops[k];
+        if (op.nbytes == 0 || op.dst_off > cap || op.nbytes > cap - op.dst_off) return TG_ERR_INVALID;
+        if (op.dst_off % store.align() != 0) return TG_ERR_INVALID;
+        if (op.kind == 0) {
+            if (op.src_off > cap || op.nbytes > cap - op.src_off) return TG_ERR_INVALID;
+            if (pl.alias) {
+                if (op.dst_off != op.src_off) return TG_ERR_INVALID;
+                continue;                                   // nothing is written
+            }
+        } else if (op.src_off > pl.host_bytes || op.nbytes > pl.host_bytes - op.src_off) {
+            return TG_ERR_INVALID;
+        }
+        dst.push_back({op.dst_off, op.dst_off + op.nbytes});
+    }
+    // moved tensors end up where the plan says; new slots may not touch them
+    for (const tg::Move &m : pl.moves) {
+        if (m.nbytes == 0 || m.old_off > cap || m.nbytes > cap - m.old_off) return TG_ERR_INVALID;
+        if (m.new_off >= m.old_off || m.new_off % store.align() != 0) return TG_ERR_INVALID;
+        dst.push_back({m.new_off, m.new_off + m.nbytes});
+    }
+    std::sort(dst.begin(), dst.end());
+    for (size_t i = 1; i < dst.size(); ++i)
+        if (dst[i].first < dst[i - 1].second) return TG_ERR_INVALID;
+    return TG_OK;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 tg_status check_model(const tg_model_desc *m, std::vector<tg::TensorIn> &tensors) {
@@ -511,6 +545,10 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     if (pl.transfer_bytes > 0 && !pl.host_base) return TG_ERR_INVALID;
     hipStream_t sg = static_cast<hipStream_t>(stream_gather), sh = static_cast<hipStream_t>(stream_h2d);
     const uint64_t base = store.base();
+    {
+        const tg_status rc = validate_plan(pl, store);
+        if (rc != TG_OK) return rc;
+    }
 
     std::lock_guard<std::mutex> lock(g_scratch.mu);
     {
