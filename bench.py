@@ -304,6 +304,8 @@ def main():
                    "tensors": sum(len(w.models[n].tensors) for n in (names if w.streamed else names[:1])),
                    "pool_bytes": w.pool_bytes,
                    "reused_fraction": round(sum(rec[1]["reused_bytes"] for rec in recs) / total_bytes, 4),
+                   "reused_tensors": int(sum(sum(1 for op in rec[1]["ops"] if op[0] == 0) for rec in recs) / args.steps),
+                   "designated_shared_tensors": sum(w.designated_shared.values()) // max(1, len(w.designated_shared)),
                    "verify_fingerprint": verify,
                    "plan_flags": sorted(k for k, v in w.load_flags.items() if v),
                    "model_cache": ("streamed in %d parts (pinned host memory is capped below the model size); "
