@@ -108,6 +108,8 @@ class WorkloadRunner:
             else:
                 _, name, evict = act
                 self.pool.release(self.w.models[name].model_id, evict)
+        for name, (p, b, a) in self.w.costs.items():
+            self.pool.set_model_cost(self.w.models[name].model_id, p, b, a)
 
     def load(self, name: str, confirm: bool = False, verify: bool = False, **flags):
         """Loads a model; plan flags default to the workload's for its measured loads."""

@@ -76,6 +76,8 @@ class Workload:
     # True when a measured load changes the pool beyond what releasing the model
     # undoes (it moved or evicted residents): the setup is replayed before each step
     rebuild_each_step: bool = False
+    # eviction-cost parameters (miss probability, load bandwidth, sensitivity) by model name
+    costs: Dict[str, Tuple[float, float, float]] = field(default_factory=dict)
 
 
 def seed_for(cfg: int, model: int, k: int) -> int:
@@ -262,6 +264,26 @@ def workload_neox20b() -> Workload:
                     setup, ["M20"], {"M20": n_shared})
 
 
+def workload_neox20b_tight(pool_gb: float = 72.0) -> Workload:
+    """Config 4's models in a pool that is too small: the five residents
+    (59.4 GB, all retained, none running) leave 12.6 GB free and the 20B model
+    needs 28.7 GB of new slots in alias mode.  Stage 1 has to evict by cost,
+    Stage 2 has to merge what eviction leaves fragmented.  Cost parameters per
+    resident are in `costs` (miss probability, bandwidth, sensitivity)."""
+    base = workload_neox20b()
+    models = {k: v for k, v in base.models.items() if not k.startswith("F")}
+    setup: List[tuple] = []
+    for nm in ("R1", "R2", "R3", "R4", "R5"):
+        setup += [("load", nm), ("release", nm, False)]
+    w = Workload("neox-20b-tight-pool", int(pool_gb * 1e9) // 256 * 256, 256, models, setup, ["M20"],
+                 dict(base.designated_shared))
+    w.load_flags = {"evict": True, "merge": True, "alias": True, "pack_text": True}
+    w.rebuild_each_step = True
+    w.costs = {"R1": (1.0, 57e9, 1.0), "R2": (0.8, 57e9, 1.0), "R3": (0.2, 57e9, 1.0),
+               "R4": (0.5, 57e9, 1.0), "R5": (1.0, 57e9, 1.0)}
+    return w
+
+
 def split_model(spec: ModelSpec, max_bytes: int, id_base: int) -> List[ModelSpec]:
     """Cuts a model into parts of consecutive tensors, each at most max_bytes
     (a Model Cache smaller than the model streams it part by part).  Part p is
@@ -349,6 +371,7 @@ WORKLOADS = {
     "gpt1b": workload_gpt1b,
     "llama7b": workload_llama7b,
     "neox20b": workload_neox20b,
+    "neox20b-tight": workload_neox20b_tight,
     "merge": workload_merge,
     "merge-listing": lambda: workload_merge(pack_text=False),
     "merge-notail": lambda: workload_merge(tail_mib=0),

@@ -9,6 +9,7 @@ import torch
 
 import oracle
 from oracle import ReuseStoreOracle
+from paper_2512_01357_amd import synth
 from paper_2512_01357_amd.runner import WorkloadRunner
 
 DEV = "cuda:0"
@@ -44,6 +45,19 @@ def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
     store = ReuseStoreOracle(w.pool_bytes, w.align)
     small = all(m.nbytes <= image_limit for m in w.models.values())
     plans = {}
+    tracked = []          # (oracle entry, tensor spec) of every slot ever filled
+
+    def check_residents():
+        """Every tensor still resident (moved or not) holds the bytes it was
+        loaded with: regenerated from its seed and compared on the device."""
+        n = 0
+        for e, spec in tracked:
+            if not e.owners:
+                continue                      # evicted
+            want = synth.tensor_bytes(spec, DEV)
+            assert torch.equal(r.pool.slab[e.off:e.off + e.nbytes], want), (spec.name, e.off)
+            n += 1
+        return n
 
     def load(name):
         reg = r.materialise(name)
@@ -51,13 +65,23 @@ def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
         want = oracle_fps(host_np, reg.offs, reg.sizes)
         assert reg.fps == want, "fingerprints of %s" % name
         rows = list(zip(reg.sizes, want, reg.offs))
-        oplan = store.plan(w.models[name].model_id, rows, host_np if small else None)
-        ptrs, info = r.load(name, verify=True)
+        flags = dict(w.load_flags) if name in w.loads else {}
+        oplan = store.plan(w.models[name].model_id, rows, host_np if small else None, **flags)
+        ptrs, info = r.load(name, verify=True, **flags)
+        assert info["moves"] == [(old, new, e.nbytes) for e, old, new in oplan.moves], name
+        assert info["evictions"] == [e.off for e in oplan.evictions], name
         assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops], name
         assert info["reused_bytes"] == oplan.reused_bytes
         assert info["transfer_bytes"] == oplan.transfer_bytes
+        n_before = len(store.entries) - len(oplan.evictions)
         dsts = store.assemble(oplan, host_np if small else None)
         assert ptrs == [r.pool.base + d for d in dsts]
+        fresh = [k for k in range(len(rows)) if not (oplan.alias and oplan.hits[k] is not None)]
+        for e, k in zip(store.entries[n_before:], fresh):
+            tracked.append((e, w.models[name].tensors[k]))
+        if oplan.moves or oplan.evictions:
+            say("%s: %d evicted, %d moved; %d residents re-checked"
+                % (name, len(oplan.evictions), len(oplan.moves), check_residents()))
         host_t = r.models[name].host_tensor
         n = len(rows)
         by_size = sorted(range(n), key=lambda k: rows[k][0])
@@ -86,6 +110,9 @@ def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
         else:
             r.release(act[1], act[2])
             store.release(w.models[act[1]].model_id, act[2])
+    for name, (p, b, a) in w.costs.items():
+        r.pool.set_model_cost(w.models[name].model_id, p, b, a)
+        store.set_model_cost(w.models[name].model_id, p, b, a)
     before = store.stats()
     if w.streamed:
         for name in w.loads:
@@ -100,9 +127,11 @@ def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
             say("load %s checked" % name)
             r.release(name, True)
             store.release(w.models[name].model_id, True)
-    assert store.stats() == before
+    after = store.stats()
+    if not w.rebuild_each_step:
+        assert after == before          # releasing the model undoes the load
     a = r.pool.stats()
-    for key, v in before.items():
+    for key, v in after.items():
         assert a[key] == v, key
     r.close()
     torch.cuda.empty_cache()

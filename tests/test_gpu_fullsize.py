@@ -36,6 +36,17 @@ def test_neox_20b_fragmented_pool_full_size():
     assert min(op.dst_off for op in p.ops) < before["capacity"] - before["largest_free"]
 
 
+def test_neox_20b_into_a_pool_that_is_too_small_full_size():
+    say("full size: NeoX 20B, 72 GB pool with 59 GB retained: Stage 1 + Stage 2 + alias")
+    w = synth.workload_neox20b_tight()
+    plans, _ = run_workload_both(w)
+    p = plans["M20"]
+    assert len(p.evictions) > 1000 and p.evicted_bytes > 16e9
+    assert p.moves and p.moved_bytes < p.merge_bound
+    assert p.alias and 12.3e9 < p.reused_bytes < 12.5e9
+    assert p.reused_bytes + p.transfer_bytes == w.models["M20"].nbytes
+
+
 @pytest.mark.parametrize("reuse", [0.5])
 def test_llama3_70b_full_size(reuse):
     say("full size: Llama-3 70B, reuse %.0f %%" % (reuse * 100))
