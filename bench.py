@@ -342,6 +342,37 @@ def main():
             "GBps": round(reg.nbytes / (best * 1e-3) / 1e9, 1), "frac": round(reg.nbytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "ms": round(best, 4), "bytes": reg.nbytes, "launches": len(ms) - 1}
 
+    # the confirmation step on its own: (resident copy, fresh copy) pairs of one loaded model,
+    # both operands in HBM; and one load planned with TG_PLAN_CONFIRM (the incoming bytes are read
+    # over the host link through the pinned image's device mapping)
+    if not w.rebuild_each_step and not w.load_flags.get("alias"):
+        name = names[-1]
+        reg = r.materialise(name)
+        ptrs, info = r.load(name)
+        pairs = [(r.pool.base + op[2], r.pool.base + op[1], op[3]) for op in info["ops"] if op[0] == 0]
+        if pairs:
+            ms = []
+            for _ in range(4):
+                differs = tg.tg_compare(pairs, r.pool.stream_gather)
+                ms.append(tg.tg_last_timing()["compare_ms"])
+            if any(differs):
+                raise RuntimeError("a reused tensor differs from its source")
+            nb = sum(p[2] for p in pairs)
+            best = min(ms[1:])
+            out["compare_d2d"] = {"GBps": round(2 * nb / (best * 1e-3) / 1e9, 1),
+                                  "frac": round(2 * nb / (best * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                  "ms": round(best, 4), "pairs": len(pairs), "bytes_compared": nb}
+        r.release(name, True)
+        t0 = time.perf_counter()
+        r.load(name, confirm=True)
+        t_confirm = time.perf_counter() - t0
+        tc = tg.tg_last_timing()
+        r.release(name, True)
+        out["confirm_load"] = {"ms": round(t_confirm * 1e3, 3), "compare_ms": round(tc["compare_ms"], 3),
+                               "compare_bytes": tc["compare_bytes"],
+                               "host_side_GBps": round(tc["compare_bytes"] / (tc["compare_ms"] * 1e-3) / 1e9, 2)
+                               if tc["compare_ms"] > 0 else 0.0}
+
     if any(rec[1].get("n_moves") or rec[1].get("n_evictions") for rec in recs):
         mv_ms = sum(rec[2]["move_ms"] for rec in recs)
         mv_traffic = sum(rec[2]["move_traffic_bytes"] for rec in recs)

@@ -346,3 +346,45 @@ def test_workload_gpt_1_3b():
     p = plans["M"]
     assert p.reused_bytes + p.transfer_bytes == w.models["M"].nbytes
     assert 0.45 < p.reused_bytes / w.models["M"].nbytes < 0.60
+
+
+def test_one_tensor_larger_than_4_gib():
+    """Offsets, tile counts and word indices beyond 32 bits."""
+    say("a 5 GiB tensor")
+    import torch
+    from paper_2512_01357_amd.loader import HostArena
+    n = (5 << 30) + 24
+    arena = HostArena(n + 232)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(77)
+    step = 1 << 30
+    for at in range(0, n, step):
+        m = min(step, n - at)
+        arena.tensor[at:at + m].copy_(torch.randint(0, 256, (m,), generator=g, device=DEV, dtype=torch.uint8))
+    host = arena.numpy()
+    want = oracle.fingerprint(host[:n])
+    pool = ReusePool(11 << 30, 256, DEV)
+    reg = pool.register(1, arena, [0], [n], stage_bytes=1 << 30)
+    assert reg.fps == [want]
+    ptrs, info = pool.load(reg, verify=True)                     # from the host
+    assert [op[0] for op in info["ops"]] == [1]
+    pool.release(1)
+    reg2 = pool.register(2, arena, [0], [n], fps=[want])
+    ptrs2, info2 = pool.load(reg2, verify=True)                  # device to device
+    assert [op[0] for op in info2["ops"]] == [0] and ptrs2 != ptrs
+    for p in (ptrs[0], ptrs2[0]):
+        off = p - pool.base
+        for at in range(0, n, step):
+            m = min(step, n - at)
+            assert torch.equal(pool.slab[off + at:off + at + m], arena.tensor[at:at + m].to(DEV))
+    # the tail, through the oracle's own copy
+    mine = np.empty(4096 + 24, dtype=np.uint8)
+    oracle.copy_bytes(mine, host[n - 4120:n])
+    off = ptrs2[0] - pool.base
+    assert pool.slab[off + n - 4120:off + n].cpu().numpy().tobytes() == mine.tobytes()
+    assert tg.tg_compare([(ptrs[0], ptrs2[0], n)]) == [0]
+    pool.slab[off + n - 1] ^= 1
+    torch.cuda.synchronize()
+    assert tg.tg_compare([(ptrs[0], ptrs2[0], n)]) == [1]
+    pool.close()
+    arena.free()
