@@ -37,13 +37,14 @@ def pack(tensors, align=256):
 
 
 class Both:
-    def __init__(self, capacity):
-        self.pool = ReusePool(capacity, 256, DEV)
-        self.store = ReuseStoreOracle(capacity, 256)
+    def __init__(self, capacity, align=256):
+        self.align = align
+        self.pool = ReusePool(capacity, align, DEV)
+        self.store = ReuseStoreOracle(capacity, align)
         self.keep = []
 
     def load(self, mid, tensors, **fl):
-        host, offs = pack(tensors)
+        host, offs = pack(tensors, max(self.align, 16))
         arena = HostArena(host.size)
         arena.numpy()[:] = host
         self.keep.append(arena)
@@ -218,4 +219,34 @@ def test_random_histories_with_every_flag_real_bytes(seed):
                 got = b.pool.slab[d:d + len(t)].cpu().numpy()
                 assert got.tobytes() == t.tobytes(), (mid, d)
     b.check()
+    b.close()
+
+
+@pytest.mark.parametrize("align", [16, 4096])
+def test_other_pool_alignments(align):
+    say("pool alignment %d" % align)
+    rnd = random.Random(align)
+    b = Both(8 * MIB, align)
+    a = [rbytes(rnd, n) for n in (1, 15, 16, 17, 4095, 4096, 4097, 70000, 300001, 1 << 20)]
+    b.load(1, a)
+    b.release(1)
+    m2 = [a[i] if i % 2 else rbytes(rnd, len(a[i])) for i in range(len(a))]
+    plan, dsts = b.load(2, m2)
+    assert all(d % align == 0 for d in dsts)
+    b.release(1, evict=True)
+    b.load(3, [rbytes(rnd, 2 * MIB), a[9]], evict=True, merge=True, alias=True, pack_text=True)
+    b.close()
+
+
+def test_thousands_of_tiny_tensors_in_one_launch():
+    say("5000 tiny tensors")
+    rnd = random.Random(11)
+    b = Both(8 * MIB)
+    sizes = [rnd.choice([1, 8, 16, 24, 100, 256, 700]) for _ in range(5000)]
+    a = [rbytes(rnd, n) for n in sizes]
+    b.load(1, a)
+    b.release(1)
+    m2 = [a[i] if i % 3 else rbytes(rnd, sizes[i]) for i in range(5000)]
+    plan, _ = b.load(2, m2)
+    assert sum(1 for op in plan.ops if op.kind == 0) >= 3300
     b.close()

@@ -133,9 +133,10 @@ def test_unknown_flag_bits_are_refused():
 
 def history(seed):
     rnd = random.Random(500 + seed)
-    cap = U * rnd.choice([96, 160, 400])
-    pool = tg.tg_pool_create(FAKE_BASE, cap, 256)
-    store = ReuseStoreOracle(cap)
+    align = [256, 256, 16, 4096][seed % 4]
+    cap = align * rnd.choice([96, 160, 400]) * (256 // min(align, 256))
+    pool = tg.tg_pool_create(FAKE_BASE, cap, align)
+    store = ReuseStoreOracle(cap, align)
     contents = [(rnd.choice([40, 256, 300, 512, 1000, 1024, 2048, 3000, 6000]), i) for i in range(30)]
     running, retained, next_id = [], [], 1
     n_evict = n_move = n_alias = 0
