@@ -155,13 +155,13 @@ typedef struct {
     float    compare_ms;      /* compare kernel of the last tg_compare / confirming tg_plan */
     float    gather_ms;       /* gather kernel of the last tg_assemble */
     float    h2d_ms;          /* first to last host-to-device copy of the last tg_assemble */
-    float    verify_ms;       /* fingerprint kernel of the last verifying tg_assemble */
+    float    verify_ms;       /* fingerprint kernels of the last verifying tg_assemble, summed */
     float    plan_host_ms;    /* host time of the last tg_plan (steady clock) */
     uint64_t fingerprint_bytes, compare_bytes, gather_bytes, h2d_bytes, verify_bytes;
     uint32_t h2d_copies;      /* hipMemcpyAsync calls issued by the last tg_assemble */
     uint32_t move_launches;   /* copy launches the merge moves of the last tg_assemble took */
     float    move_ms;         /* first to last merge-move launch of the last tg_assemble */
-    float    reserved;
+    uint32_t verify_launches; /* fingerprint launches of the last verifying tg_assemble (verify_ms is their sum) */
     uint64_t move_bytes;      /* bytes of the tensors moved */
     uint64_t move_traffic_bytes; /* bytes read + written by the move launches (staged stretches count twice) */
 } tg_timing;
@@ -292,9 +292,12 @@ void tg_plan_free(tg_load_plan *plan);
  * one Tensor Mapping row per new slot is added (aliased rows gain an owner),
  * the model's rows count as in use, the generation advances.
  * out_dev_ptrs [host], if not NULL, receives n_tensors [device] addresses.
- * With TG_ASSEMBLE_VERIFY the slots are fingerprinted (one launch on
- * stream_gather) before committing and TG_ERR_CORRUPT is returned, without
- * committing, if any differs from its descriptor.
+ * With TG_ASSEMBLE_VERIFY every slot is fingerprinted on stream_gather before
+ * committing -- what the gather wrote right after the gather, the transferred
+ * tensors in up to four batches, each as soon as its copies have landed, so
+ * that only the last batch's fingerprint is left when the transfer ends --
+ * and TG_ERR_CORRUPT is returned, without committing, if any differs from its
+ * descriptor.
  * TG_ERR_STALE if the pool's generation is not the plan's.  A plan can be
  * assembled once.  The two streams may be the same stream.
  */

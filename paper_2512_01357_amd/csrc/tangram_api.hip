@@ -26,7 +26,7 @@ using tgk::u64;
 
 // Loads in flight per lane (U) and resident workgroups per compute unit for
 // each kernel.  Chosen by measurement on MI355X; see tg_set_tuning.
-tg_tuning g_tune = {4, 2, 8, 2, 4, 2, 0};
+tg_tuning g_tune = {4, 2, 8, 1, 4, 2, 0};
 
 bool g_profiling = false;
 tg_timing g_timing = {};
@@ -38,6 +38,14 @@ constexpr size_t kBounceBytes = size_t(128) << 20;
 // small to be worth their launch cost and the stretch is staged.
 constexpr uint64_t kDirectShift = uint64_t(32) << 20;
 
+// A verifying tg_assemble cuts the host-to-device copies into this many batches
+// and fingerprints each as soon as it has landed.
+constexpr size_t kVerifyBatches = 4;
+// Events: 0-1 gather, 2-3 host-to-device stream, 4-5 moves, 6.. one pair per
+// verification group (1 + kVerifyBatches of them), then one per batch.
+constexpr int kBatchEvent0 = 6 + 2 * int(1 + kVerifyBatches);
+constexpr int kEvents = kBatchEvent0 + int(kVerifyBatches);
+
 // Library-owned scratch: one pinned staging buffer and one device buffer that
 // hold a launch's descriptor table, tile prefix and result words.
 struct Scratch {
@@ -45,7 +53,7 @@ struct Scratch {
     void *h = nullptr, *d = nullptr;
     size_t cap = 0;
     int cu_count = 0;
-    hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev[kEvents] = {};
     void *bounce = nullptr;             // staging for moves whose source and destination overlap
 
     tg_status init() {
@@ -571,9 +579,17 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     // Host-to-device list, in destination order; copies adjacent on both sides
     // (the slot padding included) are merged into one (Section 4 groups
     // adjacent tensors into large copies).
-    struct H2D { uint64_t dst, src, len, padded; };
+    struct H2D { uint64_t dst, src, len, padded; std::vector<u32> ops; };
     std::vector<H2D> h2d;
     std::vector<tgk::Copy> copies;
+    const bool verify = (flags & TG_ASSEMBLE_VERIFY) != 0;
+    // Verification groups: spans to fingerprint once the bytes are in place.
+    // Group 0 holds what the gather launch writes (and aliased hits, already
+    // in place); the host-to-device copies are cut into a few batches, each
+    // verified on stream A as soon as its copies are done on stream B, so only
+    // the last batch's fingerprint is left when the transfer ends.
+    struct FpGroup { std::vector<u32> ops; size_t desc_off = 0, prefix_off = 0, result_off = 0; u32 tiles = 0; u64 bytes = 0; };
+    std::vector<FpGroup> groups(1);
     void *host_dev = nullptr;
     const uint64_t small = g_tune.h2d_kernel_max_bytes;
     if (small > 0 && pl.host_base &&
@@ -584,37 +600,65 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     for (size_t k = 0; k < pl.ops.size(); ++k) {
         const tg::Op &op = pl.ops[k];
         if (op.kind == 0) {
+            groups[0].ops.push_back(u32(k));
             if (pl.alias) continue;                      // used where it lies: nothing to copy
             copies.push_back(tgk::Copy{base + op.dst_off, base + op.src_off, op.nbytes});
         } else if (host_dev && op.nbytes <= small &&
                    ((uintptr_t(host_dev) + op.src_off) & 15u) == 0) {
             // small missing tensors ride in the gather launch, read through the
             // pinned buffer's device mapping, instead of one DMA call each
+            groups[0].ops.push_back(u32(k));
             copies.push_back(tgk::Copy{base + op.dst_off, u64(uintptr_t(host_dev)) + op.src_off, op.nbytes});
         } else {
-            h2d.push_back(H2D{op.dst_off, op.src_off, op.nbytes, store.round_up(op.nbytes)});
+            h2d.push_back(H2D{op.dst_off, op.src_off, op.nbytes, store.round_up(op.nbytes), {u32(k)}});
         }
     }
     std::sort(h2d.begin(), h2d.end(), [](const H2D &a, const H2D &b) { return a.dst < b.dst; });
     std::vector<H2D> merged;
+    u64 h2d_total = 0;
     for (const H2D &c : h2d) {
+        h2d_total += c.len;
         if (!merged.empty()) {
             H2D &m = merged.back();
             if (m.dst + m.padded == c.dst && m.src + m.padded == c.src) {
                 m.len = m.padded + c.len;
                 m.padded += c.padded;
+                m.ops.push_back(c.ops[0]);
                 continue;
             }
         }
         merged.push_back(c);
     }
+    // batch_end[j] = index one past the last merged copy of batch j
+    std::vector<size_t> batch_end;
+    if (!merged.empty()) {
+        const size_t nb = verify ? std::min<size_t>(kVerifyBatches, merged.size()) : 1;
+        u64 acc = 0;
+        for (size_t i = 0; i < merged.size(); ++i) {
+            acc += merged[i].len;
+            const size_t done = batch_end.size();
+            if (i + 1 == merged.size() || (done + 1 < nb && acc * nb >= h2d_total * (done + 1)))
+                batch_end.push_back(i + 1);
+        }
+        if (verify) {
+            size_t from = 0;
+            for (size_t e : batch_end) {
+                FpGroup g;
+                for (size_t i = from; i < e; ++i) g.ops.insert(g.ops.end(), merged[i].ops.begin(), merged[i].ops.end());
+                groups.push_back(std::move(g));
+                from = e;
+            }
+        }
+    }
     u64 gather_bytes = 0;
     for (const auto &c : copies) gather_bytes += c.nbytes;
     if (!copies.empty()) launches.push_back(copies);
 
-    // ---- one table upload for every copy launch of this call
+    // ---- one table upload for every launch of this call
     const u32 U = pick_u(g_tune.gather_unroll);
     const u64 tile = tile_for(tgk::kCopyThreads, U);
+    const u32 FU = pick_u(g_tune.fingerprint_unroll);
+    const u64 fp_tile = tile_for(tgk::kReadThreads, FU);
     struct Placed { size_t desc_off, prefix_off; u32 n, tiles; };
     std::vector<Placed> placed(launches.size());
     size_t table_bytes = 0;
@@ -625,7 +669,22 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         placed[i].n = u32(launches[i].size());
         table_bytes += L.total;
     }
-    if (!launches.empty()) {
+    size_t results_off = 0, results_words = 0;
+    if (verify) {
+        for (FpGroup &g : groups) {
+            const TableLayout L = table_layout(g.ops.size(), sizeof(tgk::Span), 0);
+            g.desc_off = table_bytes + L.desc_off;
+            g.prefix_off = table_bytes + L.prefix_off;
+            table_bytes += L.total;
+        }
+        results_off = table_bytes;                       // one result word per tensor, group after group
+        for (FpGroup &g : groups) {
+            g.result_off = results_off + results_words * sizeof(u64);
+            results_words += g.ops.size();
+        }
+        table_bytes += align_up(results_words * sizeof(u64), 256);
+    }
+    if (table_bytes > 0) {
         tg_status rc = g_scratch.ensure(table_bytes);
         if (rc != TG_OK) return rc;
         char *h = static_cast<char *>(g_scratch.h);
@@ -636,7 +695,27 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
                 return TG_ERR_INVALID;
             placed[i].tiles = hp[launches[i].size()];
         }
-        TG_HIP(hipMemcpyAsync(g_scratch.d, g_scratch.h, table_bytes, hipMemcpyHostToDevice, sg));
+        if (verify) {
+            for (FpGroup &g : groups) {
+                if (g.ops.empty()) continue;
+                tgk::Span *hs = reinterpret_cast<tgk::Span *>(h + g.desc_off);
+                for (size_t i = 0; i < g.ops.size(); ++i) {
+                    hs[i].ptr = base + pl.ops[g.ops[i]].dst_off;
+                    hs[i].nbytes = pl.ops[g.ops[i]].nbytes;
+                    g.bytes += hs[i].nbytes;
+                }
+                u32 *hp = reinterpret_cast<u32 *>(h + g.prefix_off);
+                if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, g.ops.size(), fp_tile)) return TG_ERR_INVALID;
+                g.tiles = hp[g.ops.size()];
+            }
+        }
+        TG_HIP(hipMemcpyAsync(g_scratch.d, g_scratch.h, verify ? results_off : table_bytes,
+                              hipMemcpyHostToDevice, sg));
+        if (verify && results_words > 0) {
+            tgk::zero_words_kernel<<<dim3(u32((results_words + 255) / 256)), dim3(256), 0, sg>>>(
+                reinterpret_cast<u64 *>(static_cast<char *>(g_scratch.d) + results_off), u32(results_words));
+            TG_HIP(hipGetLastError());
+        }
     }
     auto launch_copy = [&](size_t i) -> tg_status {
         if (placed[i].tiles == 0) return TG_OK;
@@ -647,6 +726,22 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
                         reinterpret_cast<const tgk::Copy *>(d + placed[i].desc_off),
                         reinterpret_cast<const u32 *>(d + placed[i].prefix_off), placed[i].n, run));
         TG_HIP(hipGetLastError());
+        return TG_OK;
+    };
+    // fingerprint of verification group gi on stream A (events 6+2gi, 7+2gi time it)
+    auto launch_verify = [&](size_t gi) -> tg_status {
+        const FpGroup &g = groups[gi];
+        if (g.tiles == 0) return TG_OK;
+        char *d = static_cast<char *>(g_scratch.d);
+        const u32 grid = grid_for(g.tiles, g_tune.fingerprint_wgs_per_cu);
+        const u32 run = run_for(g.tiles, grid);
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[6 + 2 * gi], sg));
+        TG_FOR_U(FU, tgk::fingerprint_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, sg>>>(
+                         reinterpret_cast<const tgk::Span *>(d + g.desc_off),
+                         reinterpret_cast<const u32 *>(d + g.prefix_off), u32(g.ops.size()), run,
+                         reinterpret_cast<u64 *>(d + g.result_off)));
+        TG_HIP(hipGetLastError());
+        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[7 + 2 * gi], sg));
         return TG_OK;
     };
 
@@ -661,26 +756,48 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         if (sh != sg) TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[5], 0));
     }
 
-    // ---- gather launch (stream A)
+    // ---- gather launch (stream A), then the fingerprint of what it wrote
     if (!copies.empty()) {
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], sg));
         const tg_status rc = launch_copy(launches.size() - 1);
         if (rc != TG_OK) return rc;
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], sg));
     }
+    if (verify) {
+        const tg_status rc = launch_verify(0);
+        if (rc != TG_OK) return rc;
+    }
 
-    // ---- host-to-device copies (stream B), overlapped with the gather
+    // ---- host-to-device copies (stream B), overlapped with the gather; each
+    // batch is fingerprinted on stream A as soon as it has landed
     u64 h2d_bytes = 0;
     if (!merged.empty()) {
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[2], sh));
-        for (const H2D &c : merged) {
-            TG_HIP(hipMemcpyAsync(reinterpret_cast<void *>(uintptr_t(base + c.dst)),
-                                  static_cast<const char *>(pl.host_base) + c.src, c.len,
-                                  hipMemcpyHostToDevice, sh));
-            h2d_bytes += c.len;
+        size_t from = 0;
+        for (size_t j = 0; j < batch_end.size(); ++j) {
+            for (size_t i = from; i < batch_end[j]; ++i) {
+                const H2D &c = merged[i];
+                TG_HIP(hipMemcpyAsync(reinterpret_cast<void *>(uintptr_t(base + c.dst)),
+                                      static_cast<const char *>(pl.host_base) + c.src, c.len,
+                                      hipMemcpyHostToDevice, sh));
+                h2d_bytes += c.len;
+            }
+            from = batch_end[j];
+            if (verify) {
+                if (sh != sg) {
+                    TG_HIP(hipEventRecord(g_scratch.ev[kBatchEvent0 + j], sh));
+                    TG_HIP(hipStreamWaitEvent(sg, g_scratch.ev[kBatchEvent0 + j], 0));
+                }
+                const tg_status rc = launch_verify(1 + j);
+                if (rc != TG_OK) return rc;
+            }
         }
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[3], sh));
     }
+    if (verify && results_words > 0)
+        TG_HIP(hipMemcpyAsync(static_cast<char *>(g_scratch.h) + results_off,
+                              static_cast<char *>(g_scratch.d) + results_off, results_words * sizeof(u64),
+                              hipMemcpyDeviceToHost, sg));
 
     // ---- join
     TG_HIP(hipStreamSynchronize(sg));
@@ -701,22 +818,30 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         g_timing.move_bytes = pl.moved_bytes;
         g_timing.move_traffic_bytes = move_traffic;
         g_timing.move_launches = u32(n_move_launches);
+        if (verify) {
+            float total = 0.f;
+            u64 bytes = 0;
+            u32 launched = 0;
+            for (size_t gi = 0; gi < groups.size(); ++gi) {
+                if (groups[gi].tiles == 0) continue;
+                TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[6 + 2 * gi], g_scratch.ev[7 + 2 * gi]));
+                total += ms;
+                bytes += groups[gi].bytes;
+                ++launched;
+            }
+            g_timing.verify_ms = total;
+            g_timing.verify_bytes = bytes;
+            g_timing.verify_launches = launched;
+        }
     }
 
-    // ---- optional integrity check of what now sits in the slots
-    if (flags & TG_ASSEMBLE_VERIFY) {
-        const u32 n = u32(pl.ops.size());
-        std::vector<tg_span> spans(n);
-        std::vector<uint64_t> got(n);
-        for (u32 k = 0; k < n; ++k) {
-            spans[k].ptr = reinterpret_cast<const void *>(uintptr_t(base + pl.ops[k].dst_off));
-            spans[k].nbytes = pl.ops[k].nbytes;
-        }
-        tg_status rc = fingerprint_locked(spans.data(), n, got.data(), sg, &g_timing.verify_ms,
-                                          &g_timing.verify_bytes);
-        if (rc != TG_OK) return rc;
-        for (u32 k = 0; k < n; ++k)
-            if (got[k] != pl.fps[k]) return TG_ERR_CORRUPT;
+    // ---- the integrity check proper: every slot's fingerprint against its descriptor
+    if (verify) {
+        const u64 *res = reinterpret_cast<const u64 *>(static_cast<char *>(g_scratch.h) + results_off);
+        size_t at = 0;
+        for (const FpGroup &g : groups)
+            for (u32 k : g.ops)
+                if (res[at++] != pl.fps[k]) return TG_ERR_CORRUPT;
     }
 
     // ---- commit (Section 3.1: update the mapping, return the addresses)

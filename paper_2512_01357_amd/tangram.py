@@ -79,7 +79,7 @@ class tg_timing(ctypes.Structure):
         + [(n, ctypes.c_uint64) for n in (
             "fingerprint_bytes", "compare_bytes", "gather_bytes", "h2d_bytes", "verify_bytes")]
         + [("h2d_copies", ctypes.c_uint32), ("move_launches", ctypes.c_uint32),
-           ("move_ms", ctypes.c_float), ("reserved", ctypes.c_float),
+           ("move_ms", ctypes.c_float), ("verify_launches", ctypes.c_uint32),
            ("move_bytes", ctypes.c_uint64), ("move_traffic_bytes", ctypes.c_uint64)])
 
 
