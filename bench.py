@@ -26,11 +26,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then WRITE_SIZE,
+# HBM bytes per step (the gather launch; the five verify fingerprint launches together) from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then WRITE_SIZE,
 # each scaled by what the counter reads for a plain 1 GiB elementwise kernel); measured off line
 # for the default workload, so reported only when that workload and launch configuration run.
 PMC_TRAFFIC_BYTES = {
-    "llama-7b-family": {"fingerprint": (13160600 + 25) * 1024, "gather": (6836513 + 6843000) * 1024},
+    "llama-7b-family": {"fingerprint": (13160958 + 88) * 1024, "gather": (6836467 + 6845034) * 1024},
 }
 
 
