@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration
+"""GPU parity at the full sizes of the 7B, 20B and 70B workloads, in the launch configuration
 bench.py times (default tuning, verify on): fingerprints and plans of every
 tensor against the oracle, every assembled slot against its host source, and
 oracle-assembled samples byte for byte."""
