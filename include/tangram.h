@@ -23,11 +23,16 @@
  *  - Streams are hipStream_t values passed as void* (NULL = the null stream).
  *  - Errors: every function returns a tg_status; 0 is success, negative
  *    values are errors, out-parameters are left untouched on error, and no
- *    call aborts or throws across the boundary.  A failed tg_plan or
- *    tg_assemble leaves the pool's metadata exactly as it was.
+ *    call aborts or throws across the boundary.  A failed tg_plan leaves
+ *    the pool's metadata exactly as it was; so does a failed tg_assemble,
+ *    except where its comment says otherwise (a plan that had already moved
+ *    or overwritten resident tensors when it failed).
  *  - Threading: a pool is externally synchronised (one caller at a time per
  *    pool).  tg_fingerprint / tg_compare may be called from several threads;
  *    they serialise on the library's scratch.
+ *  - Device: the library serves one GPU per process, the one that is current
+ *    at its first call that touches the device; calls made with another
+ *    device current return TG_ERR_INVALID.
  *  - All sizes and offsets are in bytes.  Integer arithmetic of the
  *    fingerprint is unsigned 64-bit and wraps.
  */
@@ -298,6 +303,10 @@ void tg_plan_free(tg_load_plan *plan);
  * that only the last batch's fingerprint is left when the transfer ends --
  * and TG_ERR_CORRUPT is returned, without committing, if any differs from its
  * descriptor.
+ * When the call fails after it has started to write (TG_ERR_CORRUPT,
+ * TG_ERR_HIP), it first waits for both streams.  A plan without evictions and
+ * moves has only written into free regions: the pool is as before and the plan
+ * may be assembled again.  Otherwise the plan is given up as by tg_abandon.
  * TG_ERR_STALE if the pool's generation is not the plan's.  A plan can be
  * assembled once.  The two streams may be the same stream.
  */
@@ -310,6 +319,18 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
  * same effect on the Region List and Tensor Mapping as tg_assemble.
  */
 tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs);
+
+/*
+ * Give up a plan after its evictions and moves have happened to the bytes in
+ * the pool but its slots could not be filled (what tg_assemble does when it
+ * fails half way; for a tg_commit caller that moves the bytes itself).  The
+ * evicted rows disappear and the moved rows change address as in a commit
+ * (Section 3.2: an evicted tensor's region may have been overwritten, a merged
+ * tensor lies at its new address); the slots meant for the model are free
+ * regions again; the model gains no rows; the generation advances and the plan
+ * is consumed.  TG_ERR_STALE / TG_ERR_INVALID as for tg_commit.
+ */
+tg_status tg_abandon(tg_pool *pool, tg_load_plan *plan);
 
 /*
  * The model instance ends.  (Section 3.1: tensors of inactive models stay

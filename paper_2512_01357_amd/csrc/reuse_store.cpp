@@ -496,6 +496,22 @@ Status ReuseStore::commit(Plan &plan, std::vector<uint64_t> &dst_offs) {
     return OK;
 }
 
+// A plan that stopped half way: what it evicted has been overwritten and what
+// it moved lies at its new address, so both are recorded; the slots it meant
+// to fill go back to the free regions and the model gains nothing.
+Status ReuseStore::abandon(Plan &plan) {
+    if (plan.consumed || plan.pool_tag != this) return ERR_INVALID;
+    if (plan.generation != generation_) return ERR_STALE;
+    for (uint64_t id : plan.evict) drop_entry(id);
+    for (const Move &m : plan.moves) entries_.at(m.entry).off = m.new_off;
+    regions_ = std::move(plan.after);
+    for (size_t k = 0; k < plan.ops.size(); ++k)
+        if (!(plan.alias && plan.hits[k] != 0)) regions_.give(plan.ops[k].dst_off);
+    plan.consumed = true;
+    ++generation_;
+    return OK;
+}
+
 Status ReuseStore::release(uint64_t model_id, bool evict) {
     auto it = models_.find(model_id);
     if (it == models_.end()) return ERR_NOTFOUND;

@@ -140,6 +140,10 @@ public:
     // Install a plan made for the current generation.
     Status commit(Plan &plan, std::vector<uint64_t> &dst_offs);
 
+    // Give up a plan whose evictions and moves have already happened to the
+    // bytes in the pool: they are installed, the plan's new slots stay free.
+    Status abandon(Plan &plan);
+
     Status release(uint64_t model_id, bool evict);
 
     Status set_model_cost(uint64_t model_id, double miss_prob, double load_bw, double alpha);

@@ -53,18 +53,20 @@ struct Scratch {
     void *h = nullptr, *d = nullptr;
     size_t cap = 0;
     int cu_count = 0;
+    int device = -1;                    // the one device this process's scratch lives on
     hipEvent_t ev[kEvents] = {};
     void *bounce = nullptr;             // staging for moves whose source and destination overlap
 
     tg_status init() {
-        if (cu_count != 0) return TG_OK;
         int dev = 0;
         TG_HIP(hipGetDevice(&dev));
+        if (cu_count != 0) return dev == device ? TG_OK : TG_ERR_INVALID;
         hipDeviceProp_t prop;
         TG_HIP(hipGetDeviceProperties(&prop, dev));
         for (auto &e : ev)
             if (!e) TG_HIP(hipEventCreate(&e));
         cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        device = dev;
         return TG_OK;
     }
     tg_status ensure(size_t bytes) {
@@ -94,6 +96,7 @@ struct Scratch {
         if (bounce) { (void)hipFree(bounce); bounce = nullptr; }
         for (auto &e : ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
         cu_count = 0;
+        device = -1;
     }
 } g_scratch;
 
@@ -484,6 +487,7 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
         lp->move_rows[i] = tg_move{m.old_off, m.new_off, m.nbytes};
     }
     *out = lp;
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
     if (g_profiling)
         g_timing.plan_host_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
     return TG_OK;
@@ -540,6 +544,11 @@ tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
         for (size_t k = 0; k < dst.size(); ++k)
             out_dev_ptrs[k] = reinterpret_cast<void *>(uintptr_t(pool->store.base() + dst[k]));
     return TG_OK;
+}
+
+tg_status tg_abandon(tg_pool *pool, tg_load_plan *plan) {
+    if (!pool || !plan) return TG_ERR_INVALID;
+    return tg_status(pool->store.abandon(plan->plan));
 }
 
 tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *stream_gather,
@@ -745,103 +754,121 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         return TG_OK;
     };
 
-    // ---- moves first (stream A); nothing may land in the pool before they are done
-    if (n_move_launches > 0) {
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[4], sg));
-        for (size_t i = 0; i < n_move_launches; ++i) {
-            const tg_status rc = launch_copy(i);
-            if (rc != TG_OK) return rc;
-        }
-        TG_HIP(hipEventRecord(g_scratch.ev[5], sg));
-        if (sh != sg) TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[5], 0));
-    }
-
-    // ---- gather launch (stream A), then the fingerprint of what it wrote
-    if (!copies.empty()) {
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], sg));
-        const tg_status rc = launch_copy(launches.size() - 1);
-        if (rc != TG_OK) return rc;
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], sg));
-    }
-    if (verify) {
-        const tg_status rc = launch_verify(0);
-        if (rc != TG_OK) return rc;
-    }
-
-    // ---- host-to-device copies (stream B), overlapped with the gather; each
-    // batch is fingerprinted on stream A as soon as it has landed
-    u64 h2d_bytes = 0;
-    if (!merged.empty()) {
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[2], sh));
-        size_t from = 0;
-        for (size_t j = 0; j < batch_end.size(); ++j) {
-            for (size_t i = from; i < batch_end[j]; ++i) {
-                const H2D &c = merged[i];
-                TG_HIP(hipMemcpyAsync(reinterpret_cast<void *>(uintptr_t(base + c.dst)),
-                                      static_cast<const char *>(pl.host_base) + c.src, c.len,
-                                      hipMemcpyHostToDevice, sh));
-                h2d_bytes += c.len;
-            }
-            from = batch_end[j];
-            if (verify) {
-                if (sh != sg) {
-                    TG_HIP(hipEventRecord(g_scratch.ev[kBatchEvent0 + j], sh));
-                    TG_HIP(hipStreamWaitEvent(sg, g_scratch.ev[kBatchEvent0 + j], 0));
-                }
-                const tg_status rc = launch_verify(1 + j);
+    // Everything that touches the pool's bytes: once this has started, a
+    // failure may leave some of the plan's writes done.
+    auto device_work = [&]() -> tg_status {
+        // ---- moves first (stream A); nothing may land in the pool before they are done
+        if (n_move_launches > 0) {
+            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[4], sg));
+            for (size_t i = 0; i < n_move_launches; ++i) {
+                const tg_status rc = launch_copy(i);
                 if (rc != TG_OK) return rc;
             }
+            TG_HIP(hipEventRecord(g_scratch.ev[5], sg));
+            if (sh != sg) TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[5], 0));
         }
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[3], sh));
-    }
-    if (verify && results_words > 0)
-        TG_HIP(hipMemcpyAsync(static_cast<char *>(g_scratch.h) + results_off,
-                              static_cast<char *>(g_scratch.d) + results_off, results_words * sizeof(u64),
-                              hipMemcpyDeviceToHost, sg));
 
-    // ---- join
-    TG_HIP(hipStreamSynchronize(sg));
-    if (sh != sg) TG_HIP(hipStreamSynchronize(sh));
-    if (g_profiling) {
-        float ms = 0.f;
-        if (!copies.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
-        g_timing.gather_ms = ms;
-        g_timing.gather_bytes = gather_bytes;
-        ms = 0.f;
-        if (!merged.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[2], g_scratch.ev[3]));
-        g_timing.h2d_ms = ms;
-        g_timing.h2d_bytes = h2d_bytes;
-        g_timing.h2d_copies = u32(merged.size());
-        ms = 0.f;
-        if (n_move_launches > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[4], g_scratch.ev[5]));
-        g_timing.move_ms = ms;
-        g_timing.move_bytes = pl.moved_bytes;
-        g_timing.move_traffic_bytes = move_traffic;
-        g_timing.move_launches = u32(n_move_launches);
+        // ---- gather launch (stream A), then the fingerprint of what it wrote
+        if (!copies.empty()) {
+            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], sg));
+            const tg_status rc = launch_copy(launches.size() - 1);
+            if (rc != TG_OK) return rc;
+            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], sg));
+        }
         if (verify) {
-            float total = 0.f;
-            u64 bytes = 0;
-            u32 launched = 0;
-            for (size_t gi = 0; gi < groups.size(); ++gi) {
-                if (groups[gi].tiles == 0) continue;
-                TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[6 + 2 * gi], g_scratch.ev[7 + 2 * gi]));
-                total += ms;
-                bytes += groups[gi].bytes;
-                ++launched;
-            }
-            g_timing.verify_ms = total;
-            g_timing.verify_bytes = bytes;
-            g_timing.verify_launches = launched;
+            const tg_status rc = launch_verify(0);
+            if (rc != TG_OK) return rc;
         }
-    }
 
-    // ---- the integrity check proper: every slot's fingerprint against its descriptor
-    if (verify) {
-        const u64 *res = reinterpret_cast<const u64 *>(static_cast<char *>(g_scratch.h) + results_off);
-        size_t at = 0;
-        for (const FpGroup &g : groups)
-            for (u32 k : g.ops)
-                if (res[at++] != pl.fps[k]) return TG_ERR_CORRUPT;
+        // ---- host-to-device copies (stream B), overlapped with the gather; each
+        // batch is fingerprinted on stream A as soon as it has landed
+        u64 h2d_bytes = 0;
+        if (!merged.empty()) {
+            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[2], sh));
+            size_t from = 0;
+            for (size_t j = 0; j < batch_end.size(); ++j) {
+                for (size_t i = from; i < batch_end[j]; ++i) {
+                    const H2D &c = merged[i];
+                    TG_HIP(hipMemcpyAsync(reinterpret_cast<void *>(uintptr_t(base + c.dst)),
+                                          static_cast<const char *>(pl.host_base) + c.src, c.len,
+                                          hipMemcpyHostToDevice, sh));
+                    h2d_bytes += c.len;
+                }
+                from = batch_end[j];
+                if (verify) {
+                    if (sh != sg) {
+                        TG_HIP(hipEventRecord(g_scratch.ev[kBatchEvent0 + j], sh));
+                        TG_HIP(hipStreamWaitEvent(sg, g_scratch.ev[kBatchEvent0 + j], 0));
+                    }
+                    const tg_status rc = launch_verify(1 + j);
+                    if (rc != TG_OK) return rc;
+                }
+            }
+            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[3], sh));
+        }
+        if (verify && results_words > 0)
+            TG_HIP(hipMemcpyAsync(static_cast<char *>(g_scratch.h) + results_off,
+                                  static_cast<char *>(g_scratch.d) + results_off, results_words * sizeof(u64),
+                                  hipMemcpyDeviceToHost, sg));
+
+        // ---- join
+        TG_HIP(hipStreamSynchronize(sg));
+        if (sh != sg) TG_HIP(hipStreamSynchronize(sh));
+        if (g_profiling) {
+            float ms = 0.f;
+            if (!copies.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
+            g_timing.gather_ms = ms;
+            g_timing.gather_bytes = gather_bytes;
+            ms = 0.f;
+            if (!merged.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[2], g_scratch.ev[3]));
+            g_timing.h2d_ms = ms;
+            g_timing.h2d_bytes = h2d_bytes;
+            g_timing.h2d_copies = u32(merged.size());
+            ms = 0.f;
+            if (n_move_launches > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[4], g_scratch.ev[5]));
+            g_timing.move_ms = ms;
+            g_timing.move_bytes = pl.moved_bytes;
+            g_timing.move_traffic_bytes = move_traffic;
+            g_timing.move_launches = u32(n_move_launches);
+            if (verify) {
+                float total = 0.f;
+                u64 bytes = 0;
+                u32 launched = 0;
+                for (size_t gi = 0; gi < groups.size(); ++gi) {
+                    if (groups[gi].tiles == 0) continue;
+                    TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[6 + 2 * gi], g_scratch.ev[7 + 2 * gi]));
+                    total += ms;
+                    bytes += groups[gi].bytes;
+                    ++launched;
+                }
+                g_timing.verify_ms = total;
+                g_timing.verify_bytes = bytes;
+                g_timing.verify_launches = launched;
+            }
+        }
+
+        // ---- the integrity check proper: every slot's fingerprint against its descriptor
+        if (verify) {
+            const u64 *res = reinterpret_cast<const u64 *>(static_cast<char *>(g_scratch.h) + results_off);
+            size_t at = 0;
+            for (const FpGroup &g : groups)
+                for (u32 k : g.ops)
+                    if (res[at++] != pl.fps[k]) return TG_ERR_CORRUPT;
+        }
+        return TG_OK;
+    };
+    {
+        const tg_status rc = device_work();
+        if (rc != TG_OK) {
+            // nothing of this call may still be running when the tables are reused
+            (void)hipStreamSynchronize(sg);
+            if (sh != sg) (void)hipStreamSynchronize(sh);
+            (void)hipGetLastError();
+            // evicted tensors may have been overwritten and moved ones have moved:
+            // record that much, so that the mapping describes the pool's bytes
+            if (!pl.moves.empty() || !pl.evict.empty()) (void)store.abandon(pl);
+            return rc;
+        }
     }
 
     // ---- commit (Section 3.1: update the mapping, return the addresses)
@@ -881,24 +908,28 @@ tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double 
 }
 
 void tg_set_profiling(int on) {
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
     g_profiling = on != 0;
     g_timing = tg_timing{};
 }
 
 tg_status tg_last_timing(tg_timing *out) {
     if (!out) return TG_ERR_INVALID;
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
     *out = g_timing;
     return TG_OK;
 }
 
 tg_status tg_set_tuning(const tg_tuning *t) {
     if (!t) return TG_ERR_INVALID;
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
     g_tune = *t;
     return TG_OK;
 }
 
 tg_status tg_get_tuning(tg_tuning *t) {
     if (!t) return TG_ERR_INVALID;
+    std::lock_guard<std::mutex> lock(g_scratch.mu);
     *t = g_tune;
     return TG_OK;
 }

@@ -284,24 +284,54 @@ def workload_neox20b_tight(pool_gb: float = 72.0) -> Workload:
     return w
 
 
-def split_model(spec: ModelSpec, max_bytes: int, id_base: int) -> List[ModelSpec]:
-    """Cuts a model into parts of consecutive tensors, each at most max_bytes
-    (a Model Cache smaller than the model streams it part by part).  Part p is
-    a model of its own, named "<name>.p<p>", with id id_base + p."""
-    parts: List[List[TensorSpec]] = [[]]
-    size = 0
-    for t in spec.tensors:
-        if parts[-1] and size + t.nbytes > max_bytes:
-            parts.append([])
-            size = 0
-        parts[-1].append(t)
-        size += t.nbytes
+def split_model(spec: ModelSpec, max_bytes: int, id_base: int, interleave: bool = False) -> List[ModelSpec]:
+    """Cuts a model into parts of at most max_bytes (a Model Cache smaller than
+    the model streams it part by part).  Part p is a model of its own, named
+    "<name>.p<p>", with id id_base + p.
+
+    By default a part is a run of consecutive tensors.  With `interleave`,
+    transformer layer L goes to part L mod P and the other tensors to the
+    lightest part: siblings of a model family tend to differ in a run of
+    neighbouring layers, and dealing the layers out gives every part its share
+    of the tensors that have to be transferred, so each part's gather hides
+    under its own transfer instead of all the transfers meeting in one part."""
+    if not interleave:
+        parts: List[List[TensorSpec]] = [[]]
+        size = 0
+        for t in spec.tensors:
+            if parts[-1] and size + t.nbytes > max_bytes:
+                parts.append([])
+                size = 0
+            parts[-1].append(t)
+            size += t.nbytes
+    else:
+        n = max(1, -(-spec.nbytes // max_bytes))
+        while True:
+            parts = [[] for _ in range(n)]
+            sizes = [0] * n
+            for t in spec.tensors:
+                lay = layer_of(t.name)
+                if lay is not None:
+                    parts[lay % n].append(t)
+                    sizes[lay % n] += t.nbytes
+            for t in spec.tensors:
+                if layer_of(t.name) is None:
+                    p = sizes.index(min(sizes))
+                    parts[p].append(t)
+                    sizes[p] += t.nbytes
+            if max(sizes) <= max_bytes or n >= len(spec.tensors):
+                break
+            n += 1
+        parts = [ts for ts in parts if ts]
     return [ModelSpec("%s.p%d" % (spec.name, p), id_base + p, ts) for p, ts in enumerate(parts)]
 
 
-def workload_llama70b(reuse: float, pool_bytes: int, part_bytes: int = 48 * 10**9) -> Workload:
+def workload_llama70b(reuse: float, pool_bytes: int, part_bytes: int = 48 * 10**9,
+                      load_part_bytes: int = 50 * 10**9) -> Workload:
     """Config 5: 70B Llama-3-shaped model; a resident sibling holds the
-    designated share of its tensors (0, 50 or 90 %)."""
+    designated share of its tensors (0, 50 or 90 %).  Both go through the
+    Model Cache in parts; the measured model's layers are dealt out over its
+    parts (see split_model)."""
     shapes = llama_tensors(8192, 80, 28672, 128256, 1024)
 
     if reuse <= 0.0:
@@ -326,7 +356,7 @@ def workload_llama70b(reuse: float, pool_bytes: int, part_bytes: int = 48 * 10**
     m = make_model("M70", 2, shapes, 5, 1, gains_one=True,
                    share_from=sib if sib.tensors else None, shared=keep)
     loads = []
-    for part in split_model(m, part_bytes, 200):
+    for part in split_model(m, load_part_bytes, 200, interleave=True):
         models[part.name] = part
         loads.append(part.name)
     n_shared = sum(1 for k, (nm, _, _) in enumerate(shapes) if keep(k, nm))

@@ -100,7 +100,7 @@ _lib = None
 EXPORTS = [
     "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_fingerprint", "tg_compare",
     "tg_plan", "tg_plan_ops", "tg_plan_info", "tg_plan_moves", "tg_plan_evictions", "tg_plan_free",
-    "tg_assemble", "tg_commit", "tg_release", "tg_set_model_cost", "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
+    "tg_assemble", "tg_commit", "tg_abandon", "tg_release", "tg_set_model_cost", "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
     "tg_host_alloc", "tg_host_free", "tg_shutdown", "tg_strerror",
 ]
 
@@ -131,6 +131,7 @@ def lib() -> ctypes.CDLL:
             "tg_plan_free": ([vp], None),
             "tg_assemble": ([vp, vp, u32, vp, vp, P(vp)], i32),
             "tg_commit": ([vp, vp, P(vp)], i32),
+            "tg_abandon": ([vp, vp], i32),
             "tg_release": ([vp, u64, u32], i32),
             "tg_reuse_size": ([vp, P(tg_model_desc), ctypes.c_double, P(u64), P(ctypes.c_double)], i32),
             "tg_set_tuning": ([P(tg_tuning)], i32),
@@ -293,6 +294,10 @@ def tg_commit(pool, plan, n_tensors: int) -> List[int]:
     out = (ctypes.c_void_p * max(n_tensors, 1))()
     _check(lib().tg_commit(pool, plan, out), "tg_commit")
     return [int(out[k] or 0) for k in range(n_tensors)]
+
+
+def tg_abandon(pool, plan) -> None:
+    _check(lib().tg_abandon(pool, plan), "tg_abandon")
 
 
 def tg_release(pool, model_id: int, flags: int = 0) -> None:

@@ -77,6 +77,13 @@ int main(int argc, char **argv) {
                 if (plan.moved_bytes > plan.merge_bound && !plan.moves.empty()) fail("moved more than the bound", step);
                 std::vector<uint64_t> dst;
                 if (rng() % 10 == 0) continue;            // planned, never carried out
+                if (rng() % 12 == 0) {                    // given up half way
+                    const uint64_t free_before = store.stats().free_bytes;
+                    if (store.abandon(plan) != OK) fail("abandon failed", step);
+                    if (store.abandon(plan) != ERR_INVALID) fail("a plan was abandoned twice", step);
+                    if (store.stats().free_bytes != free_before + plan.evicted_bytes) fail("abandon: free bytes", step);
+                    continue;
+                }
                 if (store.commit(plan, dst) != OK) fail("commit failed", step);
                 if (store.commit(plan, dst) != ERR_INVALID) fail("a plan was committed twice", step);
                 running.push_back(mid);

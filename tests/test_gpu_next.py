@@ -113,6 +113,49 @@ def test_hand_derived_merge_plan_moves_real_bytes():
     b.close()
 
 
+def test_failed_verification_after_moves_and_evictions_leaves_a_consistent_pool():
+    say("verification fails on a plan that moves and evicts")
+    rnd = random.Random(77)
+    b = Both(30 * U)
+    carve(b, rnd, [(4, False), (2, True), (4, False), (6, True), (4, False), (1, True), (4, False),
+                   (1, True), (4, False)], U)
+
+    def failing_load(mid, tensors, **fl):
+        """A model whose last descriptor carries a wrong fingerprint: the library
+        gives the plan up; the oracle carries it out and drops the model at once."""
+        host, offs = pack(tensors)
+        arena = HostArena(host.size)
+        arena.numpy()[:] = host
+        b.keep.append(arena)
+        sizes = [len(t) for t in tensors]
+        fps = [oracle.fingerprint(t) for t in tensors]
+        fps[-1] ^= 1 << 40
+        reg = b.pool.register(mid, arena, offs, sizes, fps=fps)
+        oplan = b.store.plan(mid, list(zip(sizes, fps, offs)), host, **fl)
+        gen = b.pool.stats()["generation"]
+        with pytest.raises(tg.TgError) as e:
+            b.pool.load(reg, verify=True, **fl)
+        assert e.value.status == tg.TG_ERR_CORRUPT
+        assert b.pool.stats()["generation"] == gen + 1
+        b.store.assemble(oplan, host)
+        b.store.release(mid, True)
+        b.check()
+        return oplan
+
+    oplan = failing_load(9, [rbytes(rnd, 6 * U), rbytes(rnd, 5 * U - 7)], merge=True)
+    assert [(o // U, n // U) for _e, o, n in oplan.moves] == [(4, 0), (20, 16), (25, 17)]
+    # fill the pool with retained models, then a failing load that has to evict
+    for i in range(3):
+        b.load(200 + i, [rbytes(rnd, 5 * U), rbytes(rnd, U)])
+        b.release(200 + i)
+    oplan = failing_load(10, [rbytes(rnd, 3 * U), rbytes(rnd, 4 * U)], evict=True, merge=True)
+    assert oplan.evictions
+    # the pool goes on working: a good load, a reload of a survivor in place
+    b.load(11, [rbytes(rnd, 2 * U), rbytes(rnd, 700)], evict=True, merge=True)
+    b.release(11, evict=True)
+    b.close()
+
+
 def test_large_moves_straight_and_staged():
     say("merge with large shifts (straight copies) and small shifts over long tensors (staged)")
     tg.tg_set_profiling(True)

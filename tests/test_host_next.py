@@ -123,6 +123,54 @@ def test_hand_derived_eviction_and_merge_examples():
     tg.tg_pool_destroy(pool)
 
 
+def test_abandoned_plan_keeps_its_evictions_and_moves_only():
+    # F4 a2 F4 B6 F4 c1 F4 d1 F4 again: the merge happens, the model does not arrive
+    pool = tg.tg_pool_create(FAKE_BASE, 30 * U, 256)
+    layout = [(4, False), (2, True), (4, False), (6, True), (4, False), (1, True), (4, False),
+              (1, True), (4, False)]
+    kept = {}
+    for i, (units, keep) in enumerate(layout):
+        rows, hb = layout_rows([units * U], [("L", i)])
+        lp = tg.tg_plan(pool, tg.ModelDesc(100 + i, FAKE_HOST, hb, rows), 0)
+        tg.tg_commit(pool, lp, 1)
+        tg.tg_plan_free(lp)
+        tg.tg_release(pool, 100 + i, 0)
+        if keep:
+            kept[100 + i] = (rows, hb)
+    for i, (units, keep) in enumerate(layout):
+        if not keep:
+            tg.tg_release(pool, 100 + i, tg.TG_RELEASE_EVICT)
+    rows, hb = layout_rows([6 * U, 5 * U - 7], ["m0", "m1"])
+    lp = tg.tg_plan(pool, tg.ModelDesc(9, FAKE_HOST, hb, rows), tg.TG_PLAN_MERGE)
+    stale = tg.tg_plan(pool, tg.ModelDesc(10, FAKE_HOST, hb, rows), tg.TG_PLAN_MERGE)
+    assert tg.tg_plan_moves(lp) == [(4 * U, 0, 2 * U), (20 * U, 16 * U, U), (25 * U, 17 * U, U)]
+    before = tg.tg_pool_stats(pool)
+    tg.tg_abandon(pool, lp)
+    after = tg.tg_pool_stats(pool)
+    assert after["free_bytes"] == before["free_bytes"] and after["n_entries"] == before["n_entries"] == 4
+    assert after["generation"] == before["generation"] + 1 and after["n_active"] == 0
+    # regions now: a2 F8 B6 c1 d1 F12
+    assert after["n_free_regions"] == 2 and after["largest_free"] == 12 * U
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_abandon(pool, lp)
+    assert e.value.status == tg.TG_ERR_INVALID
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_abandon(pool, stale)
+    assert e.value.status == tg.TG_ERR_STALE
+    tg.tg_plan_free(lp)
+    tg.tg_plan_free(stale)
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_release(pool, 9, 0)
+    assert e.value.status == tg.TG_ERR_NOTFOUND
+    # the survivors are found where the moves put them
+    want = {101: 0, 103: 10 * U, 105: 16 * U, 107: 17 * U}
+    for mid, (r, h) in kept.items():
+        lp = tg.tg_plan(pool, tg.ModelDesc(mid, FAKE_HOST, h, r), tg.TG_PLAN_ALIAS)
+        assert tg.tg_plan_ops(lp)[0] == [(tg.TG_OP_REUSE, want[mid], want[mid], r[0][0])]
+        tg.tg_plan_free(lp)
+    tg.tg_pool_destroy(pool)
+
+
 def test_unknown_flag_bits_are_refused():
     pool = tg.tg_pool_create(FAKE_BASE, 4096, 256)
     with pytest.raises(tg.TgError) as e:
@@ -163,6 +211,16 @@ def history(seed):
             n_alias += sum(1 for h in op.hits if h is not None) if fl["alias"] else 0
             if rnd.random() < 0.1:
                 tg.tg_plan_free(lp)
+            elif mid == next_id and rnd.random() < 0.12:
+                # giving a plan up == carrying it out and evicting the (new) model at once
+                tg.tg_abandon(pool, lp)
+                store.assemble(op)
+                store.release(mid, True)
+                with pytest.raises(tg.TgError) as e:
+                    tg.tg_commit(pool, lp, len(rows))
+                assert e.value.status == tg.TG_ERR_INVALID
+                tg.tg_plan_free(lp)
+                next_id += 1
             else:
                 ptrs = tg.tg_commit(pool, lp, len(rows))
                 dsts = store.assemble(op)
