@@ -13,6 +13,7 @@ roofline of the dominant kernel, the other kernels' figures, the host-link
 figure and the CPU oracle's rate on a bounded sample of the same workload.
 """
 import argparse
+import gc
 import json
 import os
 import statistics
@@ -250,6 +251,10 @@ def main():
     torch.cuda.synchronize()
     recs = []
     timed_total = 0.0
+    # no garbage-collector pass inside the timed region (as timeit does): a full pass over
+    # everything torch has imported takes tens of ms, more than 100 loads of the smallest workload
+    gc.collect()
+    gc.disable()
     t_begin = time.perf_counter()
     for i in range(args.steps):
         out, timed = step(args.warmup + i)
@@ -258,6 +263,7 @@ def main():
             timed_total += timed
     torch.cuda.synchronize()
     elapsed = timed_total if (w.streamed or w.rebuild_each_step) else time.perf_counter() - t_begin
+    gc.enable()
     st1 = r.pool.stats()
     if any(st1[k] != st0[k] for k in st0 if k != "generation"):
         raise RuntimeError("pool did not return to its starting state: %s vs %s" % (st1, st0))

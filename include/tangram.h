@@ -299,8 +299,9 @@ void tg_plan_free(tg_load_plan *plan);
  * out_dev_ptrs [host], if not NULL, receives n_tensors [device] addresses.
  * With TG_ASSEMBLE_VERIFY every slot is fingerprinted on stream_gather before
  * committing -- what the gather wrote right after the gather, the transferred
- * tensors in up to four batches, each as soon as its copies have landed, so
- * that only the last batch's fingerprint is left when the transfer ends --
+ * tensors in up to four batches of at least 64 MiB, each as soon as its copies
+ * have landed, so that only the last batch's fingerprint is left when the
+ * transfer ends (a smaller transfer is waited for by the host instead) --
  * and TG_ERR_CORRUPT is returned, without committing, if any differs from its
  * descriptor.
  * When the call fails after it has started to write (TG_ERR_CORRUPT,
@@ -369,8 +370,10 @@ tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double 
  * 256 lanes x 16 B x unroll); *_wgs_per_cu is the number of 256-lane
  * workgroups launched per compute unit.  h2d_kernel_max_bytes > 0 lets missing
  * tensors up to that size be fetched by the gather kernel through the pinned
- * buffer's device mapping instead of one copy-engine call each.  The defaults
- * are the measured optimum on MI355X; results never depend on these values.
+ * buffer's device mapping instead of one copy-engine call each (default
+ * 64 KiB: such a copy takes about 1 us on the link and about 10 us to issue).
+ * The defaults are the measured optimum on MI355X; results never depend on
+ * these values.
  */
 typedef struct {
     uint32_t fingerprint_unroll, fingerprint_wgs_per_cu;

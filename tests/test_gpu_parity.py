@@ -115,6 +115,14 @@ def test_fingerprint_rejects_bad_arguments():
     with pytest.raises(tg.TgError) as e:
         tg.tg_fingerprint([(0, 64)])
     assert e.value.status == tg.TG_ERR_INVALID
+    # lengths whose tile count does not fit are refused on the host, before any launch
+    for nbytes in ((1 << 64) - 1, (1 << 64) - 4096, 1 << 50):
+        with pytest.raises(tg.TgError) as e:
+            tg.tg_fingerprint([(buf.data_ptr(), 64), (buf.data_ptr(), nbytes)])
+        assert e.value.status == tg.TG_ERR_INVALID
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_compare([(buf.data_ptr(), buf.data_ptr(), (1 << 64) - 1)])
+    assert e.value.status == tg.TG_ERR_INVALID
 
 
 def test_fingerprint_on_a_stream_and_single_bit_flip():
@@ -252,10 +260,11 @@ def test_load_small_models_ragged_sizes(gather_unroll):
         tg.tg_set_tuning(**old)
 
 
-def test_small_missing_tensors_through_the_gather_kernel():
-    say("small H2D via kernel")
+@pytest.mark.parametrize("limit", [0, 65536, 1 << 20])
+def test_small_missing_tensors_through_the_gather_kernel(limit):
+    say("small H2D via kernel, up to %d bytes (0: every missing tensor by the copy engine)" % limit)
     old = tg.tg_get_tuning()
-    tg.tg_set_tuning(h2d_kernel_max_bytes=65536)
+    tg.tg_set_tuning(h2d_kernel_max_bytes=limit)
     try:
         rnd = random.Random(41)
         b = Both(32 << 20)

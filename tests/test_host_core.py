@@ -236,6 +236,13 @@ def test_plan_parity_llama70b(reuse):
     assert len(w.loads) == 3 and sum(len(w.models[n].tensors) for n in w.loads) == 723
     assert reused + transfer == total
     assert 141.0e9 < total < 141.2e9
+    # the parts hold every tensor once, fit the Model Cache, and each has its share of the transfers
+    names = [t.name for n in w.loads for t in w.models[n].tensors]
+    assert len(set(names)) == 723
+    assert all(w.models[n].nbytes <= 50 * 10**9 for n in w.loads)
+    if reuse < 1.0:
+        share = [out[n].transfer_bytes / transfer for n in w.loads]
+        assert min(share) > 0.2, share
     if reuse == 0.0:
         # nothing designated; later parts still find the all-ones norm gains of earlier parts
         assert reused == sum(t.nbytes for n in w.loads[1:] for t in w.models[n].tensors if t.kind == "ones")
