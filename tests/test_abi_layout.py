@@ -1,0 +1,60 @@
+"""The header is valid C, and the ctypes binding lays every struct out as the
+C compiler does (CPU only): sizes, field offsets, flag and status values."""
+import ctypes
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2512_01357_amd import tangram as tg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tangram.h")
+
+STRUCTS = ["tg_span", "tg_pair", "tg_tensor_desc", "tg_model_desc", "tg_plan_op", "tg_move",
+           "tg_plan_summary", "tg_stats", "tg_timing", "tg_tuning"]
+CONSTANTS = ["TG_OK", "TG_ERR_INVALID", "TG_ERR_NOSPACE", "TG_ERR_STALE", "TG_ERR_NOTFOUND", "TG_ERR_HIP",
+             "TG_ERR_NOMEM", "TG_ERR_CORRUPT", "TG_PLAN_CONFIRM", "TG_PLAN_EVICT", "TG_PLAN_MERGE",
+             "TG_PLAN_ALIAS", "TG_PLAN_PACK_TEXT", "TG_ASSEMBLE_VERIFY", "TG_RELEASE_EVICT", "TG_OP_REUSE",
+             "TG_OP_H2D"]
+
+
+def c_layout(tmp_path):
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "tangram.h"', 'int main(void) {']
+    for s in STRUCTS:
+        cls = getattr(tg, s)
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (s, s))
+        for name, _ in cls._fields_:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (s, name, s, name))
+    for c in CONSTANTS:
+        lines.append('printf("%s %%lld\\n", (long long)(%s));' % (c, c))
+    lines += ['return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.dirname(HEADER),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    return dict((k, int(v)) for k, v in (line.split() for line in out.splitlines()))
+
+
+def test_binding_structs_and_constants_match_the_header(tmp_path):
+    want = c_layout(tmp_path)
+    for s in STRUCTS:
+        cls = getattr(tg, s)
+        assert ctypes.sizeof(cls) == want[s], s
+        for name, _ in cls._fields_:
+            assert getattr(cls, name).offset == want["%s.%s" % (s, name)], (s, name)
+    for c in CONSTANTS:
+        assert getattr(tg, c) == want[c], c
+
+
+def test_every_struct_and_function_of_the_header_is_bound():
+    text = open(HEADER).read()
+    structs = set(re.findall(r"}\s*(tg_\w+)\s*;", text))
+    assert structs == set(STRUCTS)
+    funcs = set(re.findall(r"\b(tg_\w+)\s*\(", re.sub(r"/\*.*?\*/", "", text, flags=re.S)))
+    assert funcs == set(tg.EXPORTS)
+    for f in funcs:
+        assert callable(getattr(tg, f)), f

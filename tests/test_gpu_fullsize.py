@@ -47,7 +47,7 @@ def test_neox_20b_into_a_pool_that_is_too_small_full_size():
     assert p.reused_bytes + p.transfer_bytes == w.models["M20"].nbytes
 
 
-@pytest.mark.parametrize("reuse", [0.5])
+@pytest.mark.parametrize("reuse", [0.5, 0.9])
 def test_llama3_70b_full_size(reuse):
     say("full size: Llama-3 70B, reuse %.0f %%" % (reuse * 100))
     torch.cuda.empty_cache()

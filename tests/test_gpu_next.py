@@ -183,6 +183,29 @@ def test_large_moves_straight_and_staged():
     tg.tg_set_profiling(False)
 
 
+@pytest.mark.parametrize("streams", ["one side stream", "null stream", "null + side", "side + null"])
+def test_moves_gather_and_transfer_on_any_pair_of_streams(streams):
+    say("merge + gather + transfer on %s, with a transfer large enough for the pipelined verification" % streams)
+    rnd = random.Random(5)
+    b = Both(600 * MIB)
+    side = b.pool.stream_gather
+    b.pool.stream_gather, b.pool.stream_h2d = {
+        "one side stream": (side, side), "null stream": (None, None),
+        "null + side": (None, side), "side + null": (side, None)}[streams]
+    # F8 A40 F8 B24 F(rest): residents A and B are also tensors of the incoming model (gathered);
+    # the 300 MiB miss (pipelined verification: batches of >= 64 MiB) leaves room only if A, B merge
+    carve(b, rnd, [(8, False), (40, True), (8, False), (24, True), (8, False)], MIB)
+    a_bytes = b.store.image[8 * MIB][:40 * MIB].copy()
+    big = [rbytes(rnd, 100 * MIB - 16 * i) for i in range(3)]
+    filler = rbytes(rnd, 190 * MIB)
+    b.load(50, [filler])
+    b.release(50)
+    plan, _ = b.load(9, big + [a_bytes, rbytes(rnd, 4096), rbytes(rnd, 70000)], merge=True)
+    assert plan.moves and plan.ops[3].kind == 0
+    b.release(9, evict=True)
+    b.close()
+
+
 def test_eviction_then_load_real_bytes():
     say("stage 1 eviction")
     rnd = random.Random(3)
