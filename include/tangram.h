@@ -367,8 +367,9 @@ tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double 
 /*
  * Launch shape of the three streaming kernels.  *_unroll is the number of
  * independent 128-bit loads a lane issues per tile (2, 4, 8 or 16; a tile is
- * 256 lanes x 16 B x unroll); *_wgs_per_cu is the number of 256-lane
- * workgroups launched per compute unit.  h2d_kernel_max_bytes > 0 lets missing
+ * lanes x 16 B x unroll, with 256 lanes for fingerprint and compare and 1024
+ * for the gather); *_wgs_per_cu is the number of workgroups launched per
+ * compute unit.  h2d_kernel_max_bytes > 0 lets missing
  * tensors up to that size be fetched by the gather kernel through the pinned
  * buffer's device mapping instead of one copy-engine call each (default
  * 64 KiB: such a copy takes about 1 us on the link and about 10 us to issue).

@@ -87,7 +87,7 @@ def test_little_endian_words_and_zero_padded_tail(impl):
 
 
 def test_values_computed_when_the_build_was_specified():
-    for recipe, val in read_pairs(os.path.join(GOLD, "survey_fingerprints.txt")):
+    for recipe, val in read_pairs(os.path.join(GOLD, "specified_fingerprints.txt")):
         assert fingerprint(build(recipe)) == val, recipe
         assert fingerprint_py(build(recipe)) == val, recipe
 
