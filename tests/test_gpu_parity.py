@@ -125,6 +125,41 @@ def test_fingerprint_rejects_bad_arguments():
     assert e.value.status == tg.TG_ERR_INVALID
 
 
+def test_fingerprint_and_compare_from_several_threads():
+    """The header lets tg_fingerprint / tg_compare be called from several
+    threads at once (they take turns on the library's scratch)."""
+    import threading
+    say("fingerprint / compare from 4 threads, each on a stream of its own")
+    rnd = random.Random(29)
+    lengths = [16, 4096 + 8, TILE_U8 + 1, 3 * TILE_U8 + 24, (1 << 20) + 40, 7]
+    datas = [[random_bytes(rnd, n) for n in lengths] for _ in range(4)]
+    bufs = [[dev_bytes(d) for d in row] for row in datas]
+    want = [[oracle.fingerprint(d) for d in row] for row in datas]
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(t):
+        try:
+            for it in range(25):
+                spans = [(b.data_ptr(), n) for b, n in zip(bufs[t], lengths)]
+                assert tg.tg_fingerprint(spans, streams[t]) == want[t], (t, it)
+                other = bufs[(t + 1) % 4]
+                pairs = [(b.data_ptr(), b.data_ptr(), n) for b, n in zip(bufs[t], lengths)] + \
+                        [(bufs[t][4].data_ptr(), other[4].data_ptr(), lengths[4])]
+                assert tg.tg_compare(pairs, streams[t]) == [0] * len(lengths) + [1], (t, it)
+        except Exception as e:                      # noqa: BLE001 - reported by the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=120)
+    assert not any(th.is_alive() for th in threads), "a thread did not finish"
+    assert not errors, errors
+
+
 def test_fingerprint_on_a_stream_and_single_bit_flip():
     say("fingerprint stream + bit flip")
     rnd = random.Random(5)
