@@ -337,7 +337,9 @@ def main():
         ptrs, _info = r.load(name)
         spans = list(zip(ptrs, reg.sizes))
         ms = []
-        for _ in range(6):
+        # launches until 40 ms of kernel time have passed (at least 6, at most 24): after a
+        # link-bound load the first ones still run at the lower clocks
+        while len(ms) < 6 or (sum(ms) < 40.0 and len(ms) < 24):
             got = tg.tg_fingerprint(spans, r.pool.stream_gather)
             ms.append(tg.tg_last_timing()["fingerprint_ms"])
         if got != reg.fps:
@@ -346,7 +348,8 @@ def main():
         best = min(ms[1:])
         out["fingerprint_back_to_back"] = {
             "GBps": round(reg.nbytes / (best * 1e-3) / 1e9, 1), "frac": round(reg.nbytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-            "ms": round(best, 4), "bytes": reg.nbytes, "launches": len(ms) - 1}
+            "ms": round(best, 4), "bytes": reg.nbytes, "launches": len(ms),
+            "first_launch_GBps": round(reg.nbytes / (ms[0] * 1e-3) / 1e9, 1)}
 
     # a load whose tensors are all resident already (nothing crosses the host link): the same
     # model under another id, so every tensor is gathered device to device and fingerprinted
