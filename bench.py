@@ -25,7 +25,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
+HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E bandwidth
+ALU_MIX_GBPS = 17100.0        # 2.14e12 mixed words/s x 8 B: the fingerprint's arithmetic without its loads
 
 # HBM bytes per step (the gather launch; the five verify fingerprint launches together) from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then WRITE_SIZE,
 # each scaled by what the counter reads for a plain 1 GiB elementwise kernel); measured off line
@@ -294,6 +295,10 @@ def main():
                    "algorithmic_bytes_per_launch": int(2 * sum(rec[2]["gather_bytes"] for rec in recs) / len(recs)),
                    "traffic": None},
     }
+    # integer-ALU co-limit of the fingerprint: the mix alone (no loads) sustains 2.14e12 words/s
+    # on this chip (measured once with a load-free variant of the kernel), i.e. 17.1 TB/s of input
+    kernels["fingerprint"]["alu_colimit"] = {"equivalent_GBps": ALU_MIX_GBPS,
+                                             "frac": round(fp_gbps / ALU_MIX_GBPS, 4)}
     if verify and w.name in PMC_TRAFFIC_BYTES and not any(w.load_flags.values()):
         for k, v in PMC_TRAFFIC_BYTES[w.name].items():
             kernels[k]["traffic"] = v

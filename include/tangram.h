@@ -299,9 +299,10 @@ void tg_plan_free(tg_load_plan *plan);
  * out_dev_ptrs [host], if not NULL, receives n_tensors [device] addresses.
  * With TG_ASSEMBLE_VERIFY every slot is fingerprinted on stream_gather before
  * committing -- what the gather wrote right after the gather, the transferred
- * tensors in up to four batches of at least 64 MiB, each as soon as its copies
- * have landed, so that only the last batch's fingerprint is left when the
- * transfer ends (a smaller transfer is waited for by the host instead) --
+ * tensors in up to four batches of decreasing size (one per 64 MiB of transfer
+ * at most), each as soon as its copies have landed, so that only the last,
+ * smallest batch's fingerprint is left when the transfer ends (a transfer
+ * below 64 MiB is waited for by the host instead) --
  * and TG_ERR_CORRUPT is returned, without committing, if any differs from its
  * descriptor.
  * When the call fails after it has started to write (TG_ERR_CORRUPT,

@@ -152,6 +152,15 @@ u64 tile_for(u32 threads, u32 U) { return u64(threads) * 16 * U; }
 // Tiles per workgroup when `total` tiles are split into equal contiguous runs.
 u32 run_for(u32 total_tiles, u32 grid) { return (total_tiles + grid - 1) / grid; }
 
+// Waits for a stream when a call leaves early with work still enqueued, so that
+// the scratch tables are never reused (or freed) under a running kernel.
+struct DrainOnExit {
+    hipStream_t st;
+    bool armed = true;
+    explicit DrainOnExit(hipStream_t s) : st(s) {}
+    ~DrainOnExit() { if (armed) { (void)hipStreamSynchronize(st); (void)hipGetLastError(); } }
+};
+
 // ---- fingerprint over device-visible spans; scratch lock held by the caller
 tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipStream_t st,
                              float *ms_out, uint64_t *bytes_out) {
@@ -172,6 +181,7 @@ tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipS
     const u32 total_tiles = hp[n];
     u64 *d_out = reinterpret_cast<u64 *>(d + L.result_off);
     u64 *h_out = reinterpret_cast<u64 *>(h + L.result_off);
+    DrainOnExit drain(st);
     TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
     hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_out, n);
     if (total_tiles > 0) {
@@ -186,6 +196,7 @@ tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipS
     }
     TG_HIP(hipMemcpyAsync(h_out, d_out, n * sizeof(u64), hipMemcpyDeviceToHost, st));
     TG_HIP(hipStreamSynchronize(st));
+    drain.armed = false;
     if (g_profiling && ms_out) {
         float ms = 0.f;
         if (total_tiles > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
@@ -216,6 +227,7 @@ tg_status compare_locked(const tg_pair *pairs, u32 n, uint32_t *out_differs, hip
     // results are 32-bit flags; the zero kernel clears whole 64-bit words
     u32 *d_out = reinterpret_cast<u32 *>(d + L.result_off);
     u32 *h_out = reinterpret_cast<u32 *>(h + L.result_off);
+    DrainOnExit drain(st);
     TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
     const u32 words = (n + 1) / 2;
     hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((words + 255) / 256), dim3(256), 0, st,
@@ -232,6 +244,7 @@ tg_status compare_locked(const tg_pair *pairs, u32 n, uint32_t *out_differs, hip
     }
     TG_HIP(hipMemcpyAsync(h_out, d_out, n * sizeof(u32), hipMemcpyDeviceToHost, st));
     TG_HIP(hipStreamSynchronize(st));
+    drain.armed = false;
     if (g_profiling) {
         float ms = 0.f;
         if (total_tiles > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
@@ -648,12 +661,16 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     if (!merged.empty()) {
         const size_t nb = !verify ? 1 : std::max<size_t>(1, std::min<size_t>(
             std::min<size_t>(kVerifyBatches, merged.size()), size_t(h2d_total / kVerifyBatchMinBytes)));
-        u64 acc = 0;
+        // shares nb : nb-1 : ... : 1, so that little is left to fingerprint when the last copy lands
+        const u64 denom = u64(nb) * (nb + 1) / 2;
+        u64 acc = 0, cum = nb;
         for (size_t i = 0; i < merged.size(); ++i) {
             acc += merged[i].len;
             const size_t done = batch_end.size();
-            if (i + 1 == merged.size() || (done + 1 < nb && acc * nb >= h2d_total * (done + 1)))
+            if (i + 1 == merged.size() || (done + 1 < nb && acc * denom >= h2d_total * cum)) {
                 batch_end.push_back(i + 1);
+                cum += nb - (done + 1);
+            }
         }
         if (verify) {
             size_t from = 0;
@@ -699,6 +716,8 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         }
         table_bytes += align_up(results_words * sizeof(u64), 256);
     }
+    DrainOnExit drain_gather(sg);
+    drain_gather.armed = false;                 // nothing enqueued yet
     if (table_bytes > 0) {
         tg_status rc = g_scratch.ensure(table_bytes);
         if (rc != TG_OK) return rc;
@@ -726,6 +745,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         }
         TG_HIP(hipMemcpyAsync(g_scratch.d, g_scratch.h, verify ? results_off : table_bytes,
                               hipMemcpyHostToDevice, sg));
+        drain_gather.armed = true;
         if (verify && results_words > 0) {
             tgk::zero_words_kernel<<<dim3(u32((results_words + 255) / 256)), dim3(256), 0, sg>>>(
                 reinterpret_cast<u64 *>(static_cast<char *>(g_scratch.d) + results_off), u32(results_words));
@@ -878,6 +898,8 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
             return rc;
         }
     }
+
+    drain_gather.armed = false;                 // both streams have been waited for
 
     // ---- commit (Section 3.1: update the mapping, return the addresses)
     std::vector<uint64_t> dst;

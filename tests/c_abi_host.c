@@ -1,0 +1,74 @@
+/* The boundary used from plain C, host-only calls (no GPU needed): a pool over
+ * a made-up device range, two models that share a tensor, plan -> commit ->
+ * release, and the error codes of the obvious mistakes.  Prints "ok" and
+ * exits 0 when every check holds. */
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include "tangram.h"
+
+#define CHECK(cond) do { if (!(cond)) { fprintf(stderr, "line %d: %s\n", __LINE__, #cond); return 1; } } while (0)
+
+int main(void) {
+    void *base = (void *)((uintptr_t)1 << 40);
+    void *host = (void *)((uintptr_t)1 << 41);
+    tg_pool *pool = NULL;
+    CHECK(tg_pool_create(base, 4096, 256, &pool) == TG_OK && pool != NULL);
+    CHECK(tg_pool_create(base, 4096, 24, &pool) == TG_ERR_INVALID);
+    CHECK(tg_pool_create(NULL, 4096, 256, &pool) == TG_ERR_INVALID);
+
+    tg_tensor_desc a[2] = {{700, 0x1111, 0}, {256, 0x2222, 768}};
+    tg_model_desc ma = {1, host, 1024, 2, 0, a};
+    tg_load_plan *plan = NULL;
+    CHECK(tg_plan(pool, &ma, 0, NULL, &plan) == TG_OK && plan != NULL);
+    const tg_plan_op *ops = NULL;
+    uint32_t n = 0;
+    uint64_t reused = 1, transfer = 1;
+    CHECK(tg_plan_ops(plan, &ops, &n, &reused, &transfer) == TG_OK);
+    CHECK(n == 2 && reused == 0 && transfer == 956);
+    CHECK(ops[0].kind == TG_OP_H2D && ops[0].dst_off == 0 && ops[0].src_off == 0 && ops[0].nbytes == 700);
+    CHECK(ops[1].kind == TG_OP_H2D && ops[1].dst_off == 768 && ops[1].src_off == 768);
+    void *ptrs[2] = {NULL, NULL};
+    CHECK(tg_commit(pool, plan, ptrs) == TG_OK);
+    CHECK(ptrs[0] == base && ptrs[1] == (char *)base + 768);
+    CHECK(tg_commit(pool, plan, ptrs) == TG_ERR_INVALID);          /* a plan is used once */
+    tg_plan_free(plan);
+
+    tg_stats st;
+    CHECK(tg_pool_stats(pool, &st) == TG_OK);
+    CHECK(st.capacity == 4096 && st.free_bytes == 4096 - 1024 && st.n_entries == 2 && st.n_active == 2);
+    CHECK(tg_plan(pool, &ma, 0, NULL, &plan) == TG_ERR_INVALID);   /* model 1 is running */
+    CHECK(tg_release(pool, 1, 0) == TG_OK);
+    CHECK(tg_release(pool, 7, 0) == TG_ERR_NOTFOUND);
+
+    /* model 2 shares the first tensor (same fingerprint and length) */
+    tg_tensor_desc b[2] = {{700, 0x1111, 256}, {512, 0x3333, 1024}};
+    tg_model_desc mb = {2, host, 2048, 2, 0, b};
+    uint64_t reuse = 0;
+    double est = 0.0;
+    CHECK(tg_reuse_size(pool, &mb, 100.0, &reuse, &est) == TG_OK && reuse == 700 && est == 5.12);
+    CHECK(tg_plan(pool, &mb, TG_PLAN_ALIAS, NULL, &plan) == TG_OK);
+    CHECK(tg_plan_ops(plan, &ops, &n, &reused, &transfer) == TG_OK);
+    CHECK(reused == 700 && transfer == 512);
+    CHECK(ops[0].kind == TG_OP_REUSE && ops[0].dst_off == 0 && ops[0].src_off == 0);
+    tg_plan_summary info;
+    CHECK(tg_plan_info(plan, &info) == TG_OK && info.alias == 1 && info.copy_bytes == 0 && info.n_moves == 0);
+    CHECK(tg_commit(pool, plan, ptrs) == TG_OK && ptrs[0] == base);
+    tg_plan_free(plan);
+
+    /* too big for what is left, and flags nobody defined */
+    tg_tensor_desc c[1] = {{4096, 0x4444, 0}};
+    tg_model_desc mc = {3, host, 4096, 1, 0, c};
+    CHECK(tg_plan(pool, &mc, 0, NULL, &plan) == TG_ERR_NOSPACE);
+    CHECK(tg_plan(pool, &mc, 1u << 9, NULL, &plan) == TG_ERR_INVALID);
+    c[0].nbytes = 0;
+    CHECK(tg_plan(pool, &mc, 0, NULL, &plan) == TG_ERR_INVALID);
+
+    CHECK(tg_release(pool, 2, TG_RELEASE_EVICT) == TG_OK);
+    CHECK(tg_release(pool, 1, TG_RELEASE_EVICT) == TG_OK);
+    CHECK(tg_pool_stats(pool, &st) == TG_OK && st.free_bytes == 4096 && st.n_entries == 0 && st.n_free_regions == 1);
+    CHECK(strcmp(tg_strerror(TG_ERR_STALE), "plan is stale") == 0);
+    CHECK(tg_pool_destroy(pool) == TG_OK);
+    puts("ok");
+    return 0;
+}

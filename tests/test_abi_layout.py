@@ -58,3 +58,15 @@ def test_every_struct_and_function_of_the_header_is_bound():
     assert funcs == set(tg.EXPORTS)
     for f in funcs:
         assert callable(getattr(tg, f)), f
+
+
+def test_the_library_is_usable_from_plain_c(tmp_path):
+    lib_dir = os.path.dirname(tg.LIB_PATH)
+    assert os.path.exists(tg.LIB_PATH), "libtangram.so is not built"
+    exe = tmp_path / "c_abi_host"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.dirname(HEADER),
+                    os.path.join(ROOT, "tests", "c_abi_host.c"), "-o", str(exe),
+                    "-L", lib_dir, "-ltangram", "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib",
+                    "-L/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr
