@@ -86,6 +86,16 @@ def test_hand_derived_eviction_and_merge_examples():
     store.assemble(op)
     tg.tg_plan_free(lp)
     same_stats(pool, store)
+    # second round of the same example: model 3 now costs 153.6, model 1's tensors 256 and 128
+    tg.tg_set_model_cost(pool, 3, 0.3, 1.0, 1.0)
+    store.set_model_cost(3, 0.3, 1.0, 1.0)
+    rows, hb = layout_rows([512], ["n2"])
+    lp, op = plan_both(pool, store, 10, rows, hb, evict=True)
+    assert tg.tg_plan_evictions(lp) == [1024] and tg.tg_plan_ops(lp)[0][0][1] == 1024
+    tg.tg_commit(pool, lp, 1)
+    store.assemble(op)
+    tg.tg_plan_free(lp)
+    same_stats(pool, store)
     with pytest.raises(tg.TgError) as e:
         tg.tg_release(pool, 2, 0)
     assert e.value.status == tg.TG_ERR_NOTFOUND

@@ -108,6 +108,15 @@ def test_hand_derived_eviction_order():
     assert s.stats()["free_bytes"] == 0
     for t, d in zip(new, dsts):
         assert s.image[d].tobytes() == t.tobytes()
+    # Second round, pool full: C now costs 0.3*(512/1)*1 = 153.6, A's tensors still 256 and 128.
+    # A 512-byte tensor needs one eviction: A's 512 (128) goes -- not C's 512 (153.6), which a
+    # cost that multiplied by the bandwidth would pick, and not A's 1024 (256).
+    s.set_model_cost(3, 0.3, 1.0, 1.0)
+    more = [rb(rnd, 512)]
+    host, offs = pack(more)
+    plan = s.plan(10, rows(more, offs), host, evict=True)
+    assert [(e.owners, e.nbytes) for e in plan.evictions] == [([1], 512)]
+    assert s.assemble(plan, host) == [1024]
 
 
 def test_eviction_spares_running_models_and_the_plans_own_sources():
