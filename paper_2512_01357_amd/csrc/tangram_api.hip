@@ -318,6 +318,42 @@ tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
     return TG_OK;
 }
 
+// Inside one copy launch reads and writes are concurrent: no destination may
+// touch a source of the same launch, and every extent lies in the pool or in
+// the staging buffer.  A mistake in the cutting above then comes back as an
+// error code instead of moved tensors that overwrote each other.
+tg_status check_move_launches(const std::vector<std::vector<tgk::Copy>> &launches, uint64_t base, uint64_t cap) {
+    const u64 bounce = u64(reinterpret_cast<uintptr_t>(g_scratch.bounce));
+    auto inside = [&](u64 a, u64 n) {
+        const bool in_pool = a >= base && n <= cap && a - base <= cap - n;
+        const bool in_bounce = bounce != 0 && a >= bounce && n <= kBounceBytes && a - bounce <= kBounceBytes - n;
+        return in_pool || in_bounce;
+    };
+    std::vector<std::pair<u64, u64>> src, dst;
+    for (const auto &launch : launches) {
+        src.clear();
+        dst.clear();
+        for (const tgk::Copy &c : launch) {
+            if (c.nbytes == 0 || !inside(c.src, c.nbytes) || !inside(c.dst, c.nbytes)) return TG_ERR_INVALID;
+            src.push_back({c.src, c.src + c.nbytes});
+            dst.push_back({c.dst, c.dst + c.nbytes});
+        }
+        std::sort(src.begin(), src.end());
+        std::sort(dst.begin(), dst.end());
+        for (size_t i = 1; i < dst.size(); ++i)
+            if (dst[i].first < dst[i - 1].second) return TG_ERR_INVALID;
+        size_t j = 0;
+        for (const auto &d : dst) {
+            while (j < src.size() && src[j].second <= d.first) ++j;
+            // sources are not disjoint in general (none overlap here, but do not rely on it):
+            // look at every source that starts before this destination ends
+            for (size_t k = j; k < src.size() && src[k].first < d.second; ++k)
+                if (src[k].second > d.first) return TG_ERR_INVALID;
+        }
+    }
+    return TG_OK;
+}
+
 // Last check before anything is enqueued: every extent a kernel or the copy
 // engine will touch lies inside the pool (or the model's host image), and no
 // two destinations overlap.  A planner bug then comes back as an error code
@@ -599,6 +635,8 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         tg_status rc = g_scratch.ensure_bounce();
         if (rc != TG_OK) return rc;
         rc = build_move_launches(pl.moves, base, launches, move_traffic);
+        if (rc != TG_OK) return rc;
+        rc = check_move_launches(launches, base, store.capacity());
         if (rc != TG_OK) return rc;
     }
     const size_t n_move_launches = launches.size();
