@@ -376,15 +376,32 @@ tg_status validate_plan(const tg::Plan &pl, const tg::ReuseStore &store) {
         }
         dst.push_back({op.dst_off, op.dst_off + op.nbytes});
     }
+    const size_t n_slots = dst.size();                      // the rest of dst: where moved tensors land
     // moved tensors end up where the plan says; new slots may not touch them
     for (const tg::Move &m : pl.moves) {
         if (m.nbytes == 0 || m.old_off > cap || m.nbytes > cap - m.old_off) return TG_ERR_INVALID;
         if (m.new_off >= m.old_off || m.new_off % store.align() != 0) return TG_ERR_INVALID;
         dst.push_back({m.new_off, m.new_off + m.nbytes});
     }
+    std::vector<std::pair<uint64_t, uint64_t>> slots(dst.begin(), dst.begin() + n_slots);
     std::sort(dst.begin(), dst.end());
     for (size_t i = 1; i < dst.size(); ++i)
         if (dst[i].first < dst[i - 1].second) return TG_ERR_INVALID;
+    // no new slot lies where the gather reads (its sources are where the moves left them)
+    if (!pl.alias) {
+        std::sort(slots.begin(), slots.end());
+        std::vector<std::pair<uint64_t, uint64_t>> src;
+        for (const tg::Op &op : pl.ops)
+            if (op.kind == 0) src.push_back({op.src_off, op.src_off + op.nbytes});
+        std::sort(src.begin(), src.end());
+        src.erase(std::unique(src.begin(), src.end()), src.end());
+        size_t j = 0;
+        for (const auto &d : slots) {
+            while (j < src.size() && src[j].second <= d.first) ++j;
+            for (size_t k = j; k < src.size() && src[k].first < d.second; ++k)
+                if (src[k].second > d.first) return TG_ERR_INVALID;
+        }
+    }
     return TG_OK;
 }
 
