@@ -160,6 +160,26 @@ def test_fingerprint_and_compare_from_several_threads():
     assert not errors, errors
 
 
+def test_shutdown_frees_the_scratch_and_the_next_call_builds_it_again():
+    say("tg_shutdown, twice, then the library goes on working")
+    rnd = random.Random(31)
+    data = random_bytes(rnd, 3 * TILE_U8 + 24)
+    buf = dev_bytes(data)
+    want = oracle.fingerprint(data)
+    assert tg.tg_fingerprint([(buf.data_ptr(), len(data))]) == [want]
+    tg.tg_shutdown()
+    tg.tg_shutdown()
+    assert tg.tg_fingerprint([(buf.data_ptr(), len(data))]) == [want]
+    assert tg.tg_compare([(buf.data_ptr(), buf.data_ptr(), len(data))]) == [0]
+    tg.tg_shutdown()
+    b = Both(1 << 20)                       # a load right after a shutdown: events and tables are made anew
+    b.load(1, [random_bytes(rnd, 4096), random_bytes(rnd, 70000)], verify=True)
+    b.release(1)
+    b.load(2, [random_bytes(rnd, 70000)], verify=True)
+    b.check_image()
+    b.close()
+
+
 def test_fingerprint_on_a_stream_and_single_bit_flip():
     say("fingerprint stream + bit flip")
     rnd = random.Random(5)

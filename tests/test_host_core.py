@@ -324,3 +324,18 @@ def test_device_calls_fail_loudly_without_a_gpu():
     with pytest.raises(tg.TgError) as e:
         tg.tg_fingerprint([(FAKE_BASE + 8, 4096)])
     assert e.value.status == tg.TG_ERR_INVALID
+    # nothing was allocated: shutting down (twice) is harmless, and so are the host-only calls after it
+    tg.tg_shutdown()
+    tg.tg_shutdown()
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_compare([(FAKE_BASE, FAKE_BASE, 64)])
+    assert e.value.status in (tg.TG_ERR_HIP, tg.TG_ERR_NOMEM)
+    pool = tg.tg_pool_create(FAKE_BASE, 4096, 256)
+    lp = tg.tg_plan(pool, tg.ModelDesc(1, FAKE_HOST, 4096, [(512, 7, 0)]), 0)
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_assemble(pool, lp, 1, 0, None, None)          # needs the device: refused, pool untouched
+    assert e.value.status in (tg.TG_ERR_HIP, tg.TG_ERR_NOMEM)
+    assert tg.tg_pool_stats(pool)["n_entries"] == 0
+    tg.tg_commit(pool, lp, 1)
+    tg.tg_plan_free(lp)
+    tg.tg_pool_destroy(pool)
