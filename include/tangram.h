@@ -189,6 +189,33 @@ tg_status tg_pool_destroy(tg_pool *pool);
 /* Snapshot of the pool's counters.  out [host]. */
 tg_status tg_pool_stats(const tg_pool *pool, tg_stats *out);
 
+/* One region of the Region List (Section 3.2): [off, off + len) is free or
+ * holds one tensor's slot. */
+typedef struct {
+    uint64_t off;
+    uint64_t len;
+    uint32_t free;            /* 1 free, 0 allocated */
+    uint32_t reserved;
+} tg_region;
+
+/* One row of the Tensor Mapping (Section 3.1): a resident tensor. */
+typedef struct {
+    uint64_t off;             /* slot offset in the pool */
+    uint64_t nbytes;
+    uint64_t fp;
+    uint32_t n_owners;        /* models that list it (retained or running) */
+    uint32_t active_refs;     /* running models that use it; 0 = evictable */
+} tg_entry;
+
+/*
+ * The Region List in physical order, and the Tensor Mapping in ascending
+ * pool offset.  out [host] has room for cap rows; *n receives the number of
+ * rows the pool holds, and min(*n, cap) rows are written (call with cap 0 to
+ * size the array).  For inspection and tests; a load never needs them.
+ */
+tg_status tg_pool_regions(const tg_pool *pool, tg_region *out, uint32_t cap, uint32_t *n);
+tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint32_t *n);
+
 /*
  * Fingerprint.  (Section 3.1: every tensor has a fingerprint that indexes the
  * Tensor Mapping.  The function: with gamma = 0x9E3779B97F4A7C15 and

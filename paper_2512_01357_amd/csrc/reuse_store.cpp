@@ -546,6 +546,14 @@ uint64_t ReuseStore::reuse_size(const std::vector<TensorIn> &tensors) const {
     return total;
 }
 
+std::vector<const Entry *> ReuseStore::entries_by_offset() const {
+    std::vector<const Entry *> out;
+    out.reserve(entries_.size());
+    for (const auto &kv : entries_) out.push_back(&kv.second);
+    std::sort(out.begin(), out.end(), [](const Entry *a, const Entry *b) { return a->off < b->off; });
+    return out;
+}
+
 Stats ReuseStore::stats() const {
     Stats s{};
     s.capacity = capacity_;

@@ -152,6 +152,8 @@ public:
     uint64_t reuse_size(const std::vector<TensorIn> &tensors) const;
 
     Stats stats() const;
+    const RegionList &region_list() const { return regions_; }
+    std::vector<const Entry *> entries_by_offset() const;
 
 private:
     struct Model { bool active = false; std::vector<uint64_t> current, owned; };

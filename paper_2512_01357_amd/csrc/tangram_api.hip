@@ -454,6 +454,28 @@ tg_status tg_pool_stats(const tg_pool *pool, tg_stats *out) {
     return TG_OK;
 }
 
+tg_status tg_pool_regions(const tg_pool *pool, tg_region *out, uint32_t cap, uint32_t *n) {
+    if (!pool || !n || (cap > 0 && !out)) return TG_ERR_INVALID;
+    const auto &regions = pool->store.region_list().regions();
+    uint32_t i = 0;
+    for (const auto &r : regions) {
+        if (i < cap) out[i] = tg_region{r.first, r.second.len, r.second.free ? 1u : 0u, 0u};
+        ++i;
+    }
+    *n = i;
+    return TG_OK;
+}
+
+tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint32_t *n) {
+    if (!pool || !n || (cap > 0 && !out)) return TG_ERR_INVALID;
+    const std::vector<const tg::Entry *> rows = pool->store.entries_by_offset();
+    for (size_t i = 0; i < rows.size() && i < cap; ++i)
+        out[i] = tg_entry{rows[i]->off, rows[i]->nbytes, rows[i]->fp, uint32_t(rows[i]->owners.size()),
+                          rows[i]->active_refs};
+    *n = uint32_t(rows.size());
+    return TG_OK;
+}
+
 tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream) {
     if (n == 0) return TG_OK;
     if (!spans || !out_fp) return TG_ERR_INVALID;

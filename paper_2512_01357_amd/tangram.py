@@ -62,6 +62,16 @@ class tg_stats(ctypes.Structure):
         "n_entries", "n_active", "generation")]
 
 
+class tg_region(ctypes.Structure):
+    _fields_ = [("off", ctypes.c_uint64), ("len", ctypes.c_uint64), ("free", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
+
+
+class tg_entry(ctypes.Structure):
+    _fields_ = [("off", ctypes.c_uint64), ("nbytes", ctypes.c_uint64), ("fp", ctypes.c_uint64),
+                ("n_owners", ctypes.c_uint32), ("active_refs", ctypes.c_uint32)]
+
+
 class tg_move(ctypes.Structure):
     _fields_ = [("old_off", ctypes.c_uint64), ("new_off", ctypes.c_uint64), ("nbytes", ctypes.c_uint64)]
 
@@ -98,7 +108,7 @@ class TgError(RuntimeError):
 _lib = None
 
 EXPORTS = [
-    "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_fingerprint", "tg_compare",
+    "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_pool_regions", "tg_pool_entries", "tg_fingerprint", "tg_compare",
     "tg_plan", "tg_plan_ops", "tg_plan_info", "tg_plan_moves", "tg_plan_evictions", "tg_plan_free",
     "tg_assemble", "tg_commit", "tg_abandon", "tg_release", "tg_set_model_cost", "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
     "tg_host_alloc", "tg_host_free", "tg_shutdown", "tg_strerror",
@@ -120,6 +130,8 @@ def lib() -> ctypes.CDLL:
             "tg_pool_create": ([vp, u64, u32, P(vp)], i32),
             "tg_pool_destroy": ([vp], i32),
             "tg_pool_stats": ([vp, P(tg_stats)], i32),
+            "tg_pool_regions": ([vp, P(tg_region), u32, P(u32)], i32),
+            "tg_pool_entries": ([vp, P(tg_entry), u32, P(u32)], i32),
             "tg_fingerprint": ([P(tg_span), u32, P(u64), vp], i32),
             "tg_compare": ([P(tg_pair), u32, P(u32), vp], i32),
             "tg_plan": ([vp, P(tg_model_desc), u32, vp, P(vp)], i32),
@@ -185,6 +197,25 @@ def tg_pool_stats(pool) -> dict:
     st = tg_stats()
     _check(lib().tg_pool_stats(pool, ctypes.byref(st)), "tg_pool_stats")
     return {n: int(getattr(st, n)) for n, _ in tg_stats._fields_}
+
+
+def tg_pool_regions(pool) -> List[Tuple[int, int, bool]]:
+    """(offset, length, is_free) rows of the Region List in physical order."""
+    n = ctypes.c_uint32()
+    _check(lib().tg_pool_regions(pool, None, 0, ctypes.byref(n)), "tg_pool_regions")
+    arr = (tg_region * max(n.value, 1))()
+    _check(lib().tg_pool_regions(pool, arr, n.value, ctypes.byref(n)), "tg_pool_regions")
+    return [(int(arr[i].off), int(arr[i].len), bool(arr[i].free)) for i in range(n.value)]
+
+
+def tg_pool_entries(pool) -> List[Tuple[int, int, int, int, int]]:
+    """(offset, nbytes, fingerprint, owners, active refs) rows of the Tensor Mapping, by offset."""
+    n = ctypes.c_uint32()
+    _check(lib().tg_pool_entries(pool, None, 0, ctypes.byref(n)), "tg_pool_entries")
+    arr = (tg_entry * max(n.value, 1))()
+    _check(lib().tg_pool_entries(pool, arr, n.value, ctypes.byref(n)), "tg_pool_entries")
+    return [(int(arr[i].off), int(arr[i].nbytes), int(arr[i].fp), int(arr[i].n_owners), int(arr[i].active_refs))
+            for i in range(n.value)]
 
 
 # ---------------------------------------------------------------- device ops

@@ -20,6 +20,17 @@ def say(msg):
     sys.stdout.flush()
 
 
+def same_pool_state(pool, store):
+    """The library's counters, Region List and Tensor Mapping against the oracle's, row by row."""
+    from paper_2512_01357_amd import tangram as tg
+    a, b = tg.tg_pool_stats(pool), store.stats()
+    for key, v in b.items():
+        assert a[key] == v, key
+    assert tg.tg_pool_regions(pool) == [(off, length, bool(free)) for off, length, free in store.regions]
+    assert tg.tg_pool_entries(pool) == sorted((e.off, e.nbytes, e.fp, len(e.owners), e.active_refs)
+                                              for e in store.entries)
+
+
 def oracle_fps(host_np, offs, sizes, threads=16):
     """Oracle fingerprints of many tensors; the C loop releases the GIL, so a
     thread per tensor is just a way to use the host's cores."""
@@ -95,9 +106,7 @@ def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
                 mine = np.empty(nbytes, dtype=np.uint8)
                 oracle.copy_bytes(mine, host_np[off:off + nbytes])       # the oracle's assemble
                 assert oracle.bytes_equal(slot.cpu().numpy(), mine), (name, k)
-        a, b = r.pool.stats(), store.stats()
-        for key, v in b.items():
-            assert a[key] == v, key
+        same_pool_state(r.pool.pool, store)
         if after_load is not None:
             after_load(name, oplan, r)
         r.drop_host(name)
@@ -130,9 +139,7 @@ def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
     after = store.stats()
     if not w.rebuild_each_step:
         assert after == before          # releasing the model undoes the load
-    a = r.pool.stats()
-    for key, v in after.items():
-        assert a[key] == v, key
+    same_pool_state(r.pool.pool, store)
     r.close()
     torch.cuda.empty_cache()
     return plans, before

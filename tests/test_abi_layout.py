@@ -12,7 +12,7 @@ from paper_2512_01357_amd import tangram as tg
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "tangram.h")
 
-STRUCTS = ["tg_span", "tg_pair", "tg_tensor_desc", "tg_model_desc", "tg_plan_op", "tg_move",
+STRUCTS = ["tg_span", "tg_pair", "tg_tensor_desc", "tg_model_desc", "tg_plan_op", "tg_move", "tg_region", "tg_entry",
            "tg_plan_summary", "tg_stats", "tg_timing", "tg_tuning"]
 CONSTANTS = ["TG_OK", "TG_ERR_INVALID", "TG_ERR_NOSPACE", "TG_ERR_STALE", "TG_ERR_NOTFOUND", "TG_ERR_HIP",
              "TG_ERR_NOMEM", "TG_ERR_CORRUPT", "TG_PLAN_CONFIRM", "TG_PLAN_EVICT", "TG_PLAN_MERGE",

@@ -12,7 +12,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 import oracle  # noqa: E402
-from gpu_harness import DEV, say  # noqa: E402
+from gpu_harness import DEV, same_pool_state, say  # noqa: E402
 from oracle import NoSpace, ReuseStoreOracle  # noqa: E402
 from paper_2512_01357_amd import tangram as tg  # noqa: E402
 from paper_2512_01357_amd.loader import HostArena, ReusePool  # noqa: E402
@@ -74,9 +74,7 @@ class Both:
         for e in self.store.entries:
             got = self.pool.slab[e.off:e.off + e.nbytes].cpu().numpy()
             assert got.tobytes() == self.store.image[e.off][:e.nbytes].tobytes(), (e.off, e.nbytes)
-        a, b = self.pool.stats(), self.store.stats()
-        for k, v in b.items():
-            assert a[k] == v, k
+        same_pool_state(self.pool.pool, self.store)
 
     def release(self, mid, evict=False):
         self.pool.release(mid, evict)

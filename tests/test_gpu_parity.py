@@ -21,7 +21,7 @@ from paper_2512_01357_amd import synth  # noqa: E402
 from paper_2512_01357_amd import tangram as tg  # noqa: E402
 from paper_2512_01357_amd.loader import ReusePool  # noqa: E402
 from paper_2512_01357_amd.runner import WorkloadRunner  # noqa: E402
-from gpu_harness import run_workload_both  # noqa: E402
+from gpu_harness import run_workload_both, same_pool_state  # noqa: E402
 from recipes import build, read_pairs  # noqa: E402
 from test_oracle_fingerprint import colliding_pair  # noqa: E402
 
@@ -273,9 +273,7 @@ class Both:
         for e in self.store.entries:
             got = self.pool.slab[e.off:e.off + e.nbytes].cpu().numpy()
             assert got.tobytes() == self.store.image[e.off].tobytes(), (e.off, e.nbytes)
-        a, b = self.pool.stats(), self.store.stats()
-        for k, v in b.items():
-            assert a[k] == v, k
+        same_pool_state(self.pool.pool, self.store)
 
     def release(self, model_id, evict=False):
         self.pool.release(model_id, evict)

@@ -51,9 +51,13 @@ def plan_both(pool, store, mid, tensors, host_bytes, **fl):
 
 
 def same_stats(pool, store):
+    """Counters, the whole Region List and the whole Tensor Mapping, row by row."""
     a, b = tg.tg_pool_stats(pool), store.stats()
     for k, v in b.items():
         assert a[k] == v, k
+    assert tg.tg_pool_regions(pool) == [(off, length, bool(free)) for off, length, free in store.regions]
+    assert tg.tg_pool_entries(pool) == sorted((e.off, e.nbytes, e.fp, len(e.owners), e.active_refs)
+                                              for e in store.entries)
 
 
 def layout_rows(sizes, contents):
