@@ -331,7 +331,11 @@ void tg_plan_free(tg_load_plan *plan);
  * smallest batch's fingerprint is left when the transfer ends (a transfer
  * below 64 MiB is waited for by the host instead) --
  * and TG_ERR_CORRUPT is returned, without committing, if any differs from its
- * descriptor.
+ * descriptor.  Tensors that the plan moved are fingerprinted at their new
+ * addresses too, against their rows of the Tensor Mapping; one that no longer
+ * matches (it was damaged before or by the move) also ends the call with
+ * TG_ERR_CORRUPT, and its row is removed so that it is never offered for reuse
+ * again (unless a running model still uses it).
  * When the call fails after it has started to write (TG_ERR_CORRUPT,
  * TG_ERR_HIP), it first waits for both streams.  A plan without evictions and
  * moves has only written into free regions: the pool is as before and the plan

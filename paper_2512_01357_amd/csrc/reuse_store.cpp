@@ -381,7 +381,7 @@ Status ReuseStore::plan(const std::vector<TensorIn> &tensors, const std::vector<
                         if (r.free) continue;
                         if (r.off != at) {
                             const Entry &e = entries_.at(r.tag);
-                            plan.moves.push_back(Move{e.id, r.off, at, e.nbytes});
+                            plan.moves.push_back(Move{e.id, r.off, at, e.nbytes, e.fp});
                             plan.moved_bytes += e.nbytes;
                         }
                         packed.push_back(Flat{at, r.len, false, r.tag});
@@ -510,6 +510,19 @@ Status ReuseStore::abandon(Plan &plan) {
     plan.consumed = true;
     ++generation_;
     return OK;
+}
+
+void ReuseStore::drop_corrupt(const std::vector<uint64_t> &entry_ids) {
+    bool any = false;
+    for (uint64_t id : entry_ids) {
+        auto it = entries_.find(id);
+        if (it == entries_.end() || it->second.active_refs != 0) continue;
+        const uint64_t off = it->second.off;
+        drop_entry(id);
+        regions_.give(off);
+        any = true;
+    }
+    if (any) ++generation_;
 }
 
 Status ReuseStore::release(uint64_t model_id, bool evict) {

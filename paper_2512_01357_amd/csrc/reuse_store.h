@@ -89,7 +89,7 @@ struct Op {               // decision for one incoming tensor
     uint64_t dst_off, src_off, nbytes;
 };
 
-struct Move { uint64_t entry, old_off, new_off, nbytes; };
+struct Move { uint64_t entry, old_off, new_off, nbytes, fp; };
 
 struct Plan {
     uint64_t              model_id = 0;
@@ -143,6 +143,10 @@ public:
     // Give up a plan whose evictions and moves have already happened to the
     // bytes in the pool: they are installed, the plan's new slots stay free.
     Status abandon(Plan &plan);
+
+    // Remove rows whose bytes are known to be wrong (a moved tensor that no
+    // longer matches its fingerprint); rows in use by a running model are kept.
+    void drop_corrupt(const std::vector<uint64_t> &entry_ids);
 
     Status release(uint64_t model_id, bool evict);
 

@@ -46,8 +46,8 @@ constexpr size_t kVerifyBatches = 4;
 // 0.16 ms when the host joins the streams and in 1.4 ms with four event waits).
 constexpr uint64_t kVerifyBatchMinBytes = uint64_t(64) << 20;
 // Events: 0-1 gather, 2-3 host-to-device stream, 4-5 moves, 6.. one pair per
-// verification group (1 + kVerifyBatches of them), then one per batch.
-constexpr int kBatchEvent0 = 6 + 2 * int(1 + kVerifyBatches);
+// verification group (gather, the batches, the moved tensors), then one per batch.
+constexpr int kBatchEvent0 = 6 + 2 * int(2 + kVerifyBatches);
 constexpr int kEvents = kBatchEvent0 + int(kVerifyBatches);
 
 // Library-owned scratch: one pinned staging buffer and one device buffer that
@@ -692,7 +692,15 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     // in place); the host-to-device copies are cut into a few batches, each
     // verified on stream A as soon as its copies are done on stream B, so only
     // the last batch's fingerprint is left when the transfer ends.
-    struct FpGroup { std::vector<u32> ops; size_t desc_off = 0, prefix_off = 0, result_off = 0; u32 tiles = 0; u64 bytes = 0; };
+    // A last group, if the plan moves resident tensors, holds those at their new
+    // addresses (`moved`: its rows are pl.moves, not pl.ops).
+    struct FpGroup {
+        std::vector<u32> ops;
+        bool moved = false;
+        size_t desc_off = 0, prefix_off = 0, result_off = 0;
+        u32 tiles = 0;
+        u64 bytes = 0;
+    };
     std::vector<FpGroup> groups(1);
     void *host_dev = nullptr;
     const uint64_t small = g_tune.h2d_kernel_max_bytes;
@@ -759,6 +767,13 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
             }
         }
     }
+    const size_t moved_group = groups.size();           // index of the moved tensors' group, if there is one
+    if (verify && !pl.moves.empty()) {
+        FpGroup g;
+        g.moved = true;
+        groups.push_back(std::move(g));
+    }
+    auto rows_of = [&](const FpGroup &g) { return g.moved ? pl.moves.size() : g.ops.size(); };
     u64 gather_bytes = 0;
     for (const auto &c : copies) gather_bytes += c.nbytes;
     if (!copies.empty()) launches.push_back(copies);
@@ -781,7 +796,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     size_t results_off = 0, results_words = 0;
     if (verify) {
         for (FpGroup &g : groups) {
-            const TableLayout L = table_layout(g.ops.size(), sizeof(tgk::Span), 0);
+            const TableLayout L = table_layout(rows_of(g), sizeof(tgk::Span), 0);
             g.desc_off = table_bytes + L.desc_off;
             g.prefix_off = table_bytes + L.prefix_off;
             table_bytes += L.total;
@@ -789,7 +804,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         results_off = table_bytes;                       // one result word per tensor, group after group
         for (FpGroup &g : groups) {
             g.result_off = results_off + results_words * sizeof(u64);
-            results_words += g.ops.size();
+            results_words += rows_of(g);
         }
         table_bytes += align_up(results_words * sizeof(u64), 256);
     }
@@ -808,16 +823,17 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         }
         if (verify) {
             for (FpGroup &g : groups) {
-                if (g.ops.empty()) continue;
+                const size_t rows = rows_of(g);
+                if (rows == 0) continue;
                 tgk::Span *hs = reinterpret_cast<tgk::Span *>(h + g.desc_off);
-                for (size_t i = 0; i < g.ops.size(); ++i) {
-                    hs[i].ptr = base + pl.ops[g.ops[i]].dst_off;
-                    hs[i].nbytes = pl.ops[g.ops[i]].nbytes;
+                for (size_t i = 0; i < rows; ++i) {
+                    hs[i].ptr = base + (g.moved ? pl.moves[i].new_off : pl.ops[g.ops[i]].dst_off);
+                    hs[i].nbytes = g.moved ? pl.moves[i].nbytes : pl.ops[g.ops[i]].nbytes;
                     g.bytes += hs[i].nbytes;
                 }
                 u32 *hp = reinterpret_cast<u32 *>(h + g.prefix_off);
-                if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, g.ops.size(), fp_tile)) return TG_ERR_INVALID;
-                g.tiles = hp[g.ops.size()];
+                if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, rows, fp_tile)) return TG_ERR_INVALID;
+                g.tiles = hp[rows];
             }
         }
         TG_HIP(hipMemcpyAsync(g_scratch.d, g_scratch.h, verify ? results_off : table_bytes,
@@ -850,7 +866,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[6 + 2 * gi], sg));
         TG_FOR_U(FU, tgk::fingerprint_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, sg>>>(
                          reinterpret_cast<const tgk::Span *>(d + g.desc_off),
-                         reinterpret_cast<const u32 *>(d + g.prefix_off), u32(g.ops.size()), run,
+                         reinterpret_cast<const u32 *>(d + g.prefix_off), u32(rows_of(g)), run,
                          reinterpret_cast<u64 *>(d + g.result_off)));
         TG_HIP(hipGetLastError());
         if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[7 + 2 * gi], sg));
@@ -859,6 +875,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
 
     // Everything that touches the pool's bytes: once this has started, a
     // failure may leave some of the plan's writes done.
+    std::vector<uint64_t> corrupt_moved;                  // moved tensors that no longer match their rows
     auto device_work = [&]() -> tg_status {
         // ---- moves first (stream A); nothing may land in the pool before they are done
         if (n_move_launches > 0) {
@@ -869,6 +886,10 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
             }
             TG_HIP(hipEventRecord(g_scratch.ev[5], sg));
             if (sh != sg) TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[5], 0));
+            if (verify) {                                 // the moved tensors, where they are now
+                const tg_status rc = launch_verify(moved_group);
+                if (rc != TG_OK) return rc;
+            }
         }
 
         // ---- gather launch (stream A), then the fingerprint of what it wrote
@@ -952,13 +973,22 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
             }
         }
 
-        // ---- the integrity check proper: every slot's fingerprint against its descriptor
+        // ---- the integrity check proper: every slot's fingerprint against its descriptor,
+        // every moved tensor's against its row of the Tensor Mapping
         if (verify) {
             const u64 *res = reinterpret_cast<const u64 *>(static_cast<char *>(g_scratch.h) + results_off);
             size_t at = 0;
-            for (const FpGroup &g : groups)
-                for (u32 k : g.ops)
-                    if (res[at++] != pl.fps[k]) return TG_ERR_CORRUPT;
+            bool good = true;
+            for (const FpGroup &g : groups) {
+                if (g.moved) {
+                    for (const tg::Move &m : pl.moves)
+                        if (res[at++] != m.fp) { corrupt_moved.push_back(m.entry); good = false; }
+                } else {
+                    for (u32 k : g.ops)
+                        if (res[at++] != pl.fps[k]) good = false;
+                }
+            }
+            if (!good) return TG_ERR_CORRUPT;
         }
         return TG_OK;
     };
@@ -972,6 +1002,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
             // evicted tensors may have been overwritten and moved ones have moved:
             // record that much, so that the mapping describes the pool's bytes
             if (!pl.moves.empty() || !pl.evict.empty()) (void)store.abandon(pl);
+            store.drop_corrupt(corrupt_moved);
             return rc;
         }
     }

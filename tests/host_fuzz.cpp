@@ -102,6 +102,25 @@ int main(int argc, char **argv) {
                 if (s != OK && s != ERR_NOTFOUND) fail("release of a retained model failed", step);
                 retained.erase(retained.begin() + i);
             }
+            if (rng() % 40 == 0) {                        // a resident tensor turns out to be damaged
+                const auto rows = store.entries_by_offset();
+                if (!rows.empty()) {
+                    const Entry *e = rows[rng() % rows.size()];
+                    const bool in_use = e->active_refs != 0;
+                    const Stats b = store.stats();
+                    const uint64_t slot = store.round_up(e->nbytes);
+                    store.drop_corrupt({e->id});
+                    const Stats a = store.stats();
+                    if (in_use ? (a.n_entries != b.n_entries || a.free_bytes != b.free_bytes)
+                               : (a.n_entries + 1 != b.n_entries || a.free_bytes != b.free_bytes + slot))
+                        fail("drop_corrupt", step);
+                    // models that lost their last retained tensor are gone
+                    std::vector<uint64_t> still;
+                    for (uint64_t m : retained)
+                        if (store.release(m, false) == OK) still.push_back(m);
+                    retained.swap(still);
+                }
+            }
             const Stats st = store.stats();
             if (st.free_bytes > st.capacity || st.largest_free > st.free_bytes) fail("free bytes", step);
             if (st.n_regions < st.n_free_regions + st.n_entries) fail("region count", step);

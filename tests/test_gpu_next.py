@@ -181,6 +181,36 @@ def test_large_moves_straight_and_staged():
     tg.tg_set_profiling(False)
 
 
+def test_a_moved_tensor_that_no_longer_matches_its_row_is_dropped():
+    say("a resident tensor is damaged, then moved by a merging load that verifies")
+    rnd = random.Random(78)
+    b = Both(30 * U)
+    carve(b, rnd, [(4, False), (2, True), (4, False), (6, True), (4, False), (1, True), (4, False),
+                   (1, True), (4, False)], U)
+    b.pool.slab[20 * U + 5] ^= 0x10                      # model 105's tensor (moves 20 -> 16 units)
+    torch.cuda.synchronize()
+    tensors = [rbytes(rnd, 6 * U), rbytes(rnd, 5 * U - 7)]
+    host, offs = pack(tensors)
+    arena = HostArena(host.size)
+    arena.numpy()[:] = host
+    b.keep.append(arena)
+    sizes = [len(t) for t in tensors]
+    reg = b.pool.register(9, arena, offs, sizes)
+    oplan = b.store.plan(9, list(zip(sizes, reg.fps, offs)), host, merge=True)
+    assert [(o // U, n // U) for _e, o, n in oplan.moves] == [(4, 0), (20, 16), (25, 17)]
+    with pytest.raises(tg.TgError) as e:
+        b.pool.load(reg, verify=True, merge=True)
+    assert e.value.status == tg.TG_ERR_CORRUPT
+    # the moves happened, the model did not arrive, the damaged tensor is no longer offered for reuse
+    b.store.assemble(oplan, host)
+    b.store.release(9, True)
+    b.store.release(105, True)
+    b.check()
+    # without verification nobody would have noticed: the same load now goes through
+    b.load(10, tensors, merge=True)
+    b.close()
+
+
 @pytest.mark.parametrize("streams", ["one side stream", "null stream", "null + side", "side + null"])
 def test_moves_gather_and_transfer_on_any_pair_of_streams(streams):
     say("merge + gather + transfer on %s, with a transfer large enough for the pipelined verification" % streams)
