@@ -347,6 +347,27 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
                       void *stream_h2d, void **out_dev_ptrs);
 
 /*
+ * tg_assemble with its arguments in a struct, and one more: a second stream
+ * for the host-to-device copies.  With use_second_h2d_stream != 0 the copies
+ * are dealt alternately over stream_h2d and stream_h2d_second, so that one
+ * starts while the other is still running (a copy costs about 10 us to start
+ * on its stream; Section 4 groups small transfers for the same reason).  The
+ * second stream obeys the same rules as the first: it waits for the moves, its
+ * copies are part of the verification batches, and the call waits for it
+ * before it returns.  It is ignored if it equals one of the other two streams
+ * or if those two are the same stream.  flags as for tg_assemble.
+ */
+typedef struct {
+    uint32_t flags;
+    uint32_t use_second_h2d_stream;
+    void    *stream_gather;
+    void    *stream_h2d;
+    void    *stream_h2d_second;
+} tg_assemble_args;
+tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args,
+                         void **out_dev_ptrs);
+
+/*
  * Commit a plan's metadata without enqueuing any copy, for a caller that
  * fills the slots itself (or only wants the bookkeeping).  Same checks and
  * same effect on the Region List and Tensor Mapping as tg_assemble.

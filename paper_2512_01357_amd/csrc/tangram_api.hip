@@ -48,7 +48,10 @@ constexpr uint64_t kVerifyBatchMinBytes = uint64_t(64) << 20;
 // Events: 0-1 gather, 2-3 host-to-device stream, 4-5 moves, 6.. one pair per
 // verification group (gather, the batches, the moved tensors), then one per batch.
 constexpr int kBatchEvent0 = 6 + 2 * int(2 + kVerifyBatches);
-constexpr int kEvents = kBatchEvent0 + int(kVerifyBatches);
+// ... and, for the second host-to-device stream, one more per batch and one for its end
+constexpr int kBatch2Event0 = kBatchEvent0 + int(kVerifyBatches);
+constexpr int kSecondDoneEvent = kBatch2Event0 + int(kVerifyBatches);
+constexpr int kEvents = kSecondDoneEvent + 1;
 
 // Library-owned scratch: one pinned staging buffer and one device buffer that
 // hold a launch's descriptor table, tile prefix and result words.
@@ -646,7 +649,20 @@ tg_status tg_abandon(tg_pool *pool, tg_load_plan *plan) {
 
 tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *stream_gather,
                       void *stream_h2d, void **out_dev_ptrs) {
-    if (!pool || !plan) return TG_ERR_INVALID;
+    tg_assemble_args args;
+    args.flags = flags;
+    args.use_second_h2d_stream = 0;
+    args.stream_gather = stream_gather;
+    args.stream_h2d = stream_h2d;
+    args.stream_h2d_second = nullptr;
+    return tg_assemble_ex(pool, plan, &args, out_dev_ptrs);
+}
+
+tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args, void **out_dev_ptrs) {
+    if (!pool || !plan || !args) return TG_ERR_INVALID;
+    if (args->flags & ~TG_ASSEMBLE_VERIFY) return TG_ERR_INVALID;
+    const uint32_t flags = args->flags;
+    void *stream_gather = args->stream_gather, *stream_h2d = args->stream_h2d;
     tg::ReuseStore &store = pool->store;
     tg::Plan &pl = plan->plan;
     if (pl.consumed || pl.pool_tag != &store) return TG_ERR_INVALID;
@@ -654,6 +670,11 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     if (store.model_active(pl.model_id)) return TG_ERR_INVALID;
     if (pl.transfer_bytes > 0 && !pl.host_base) return TG_ERR_INVALID;
     hipStream_t sg = static_cast<hipStream_t>(stream_gather), sh = static_cast<hipStream_t>(stream_h2d);
+    // The copies may be dealt over two streams: one copy then starts while the other is still
+    // running, which hides what a copy costs to start (about 10 us each on one stream).
+    hipStream_t sh2 = args->use_second_h2d_stream ? static_cast<hipStream_t>(args->stream_h2d_second) : sh;
+    const bool dual = sh2 != sh && sh2 != sg && sh != sg;
+    if (!dual) sh2 = sh;
     const uint64_t base = store.base();
     {
         const tg_status rc = validate_plan(pl, store);
@@ -886,6 +907,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
             }
             TG_HIP(hipEventRecord(g_scratch.ev[5], sg));
             if (sh != sg) TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[5], 0));
+            if (dual) TG_HIP(hipStreamWaitEvent(sh2, g_scratch.ev[5], 0));
             if (verify) {                                 // the moved tensors, where they are now
                 const tg_status rc = launch_verify(moved_group);
                 if (rc != TG_OK) return rc;
@@ -911,24 +933,36 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
             if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[2], sh));
             size_t from = 0;
             for (size_t j = 0; j < batch_end.size(); ++j) {
+                bool used2 = false;
                 for (size_t i = from; i < batch_end[j]; ++i) {
                     const H2D &c = merged[i];
+                    const bool second = dual && (i & 1) != 0;
                     TG_HIP(hipMemcpyAsync(reinterpret_cast<void *>(uintptr_t(base + c.dst)),
                                           static_cast<const char *>(pl.host_base) + c.src, c.len,
-                                          hipMemcpyHostToDevice, sh));
+                                          hipMemcpyHostToDevice, second ? sh2 : sh));
+                    used2 = used2 || second;
                     h2d_bytes += c.len;
                 }
                 from = batch_end[j];
                 if (verify) {
                     if (sh != sg && h2d_total < kVerifyBatchMinBytes) {
                         TG_HIP(hipStreamSynchronize(sh));        // small transfer: the host joins
+                        if (used2) TG_HIP(hipStreamSynchronize(sh2));
                     } else if (sh != sg) {
                         TG_HIP(hipEventRecord(g_scratch.ev[kBatchEvent0 + j], sh));
                         TG_HIP(hipStreamWaitEvent(sg, g_scratch.ev[kBatchEvent0 + j], 0));
+                        if (used2) {
+                            TG_HIP(hipEventRecord(g_scratch.ev[kBatch2Event0 + j], sh2));
+                            TG_HIP(hipStreamWaitEvent(sg, g_scratch.ev[kBatch2Event0 + j], 0));
+                        }
                     }
                     const tg_status rc = launch_verify(1 + j);
                     if (rc != TG_OK) return rc;
                 }
+            }
+            if (dual) {                                   // stream B's end event covers the second stream
+                TG_HIP(hipEventRecord(g_scratch.ev[kSecondDoneEvent], sh2));
+                TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[kSecondDoneEvent], 0));
             }
             if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[3], sh));
         }
@@ -940,6 +974,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
         // ---- join
         TG_HIP(hipStreamSynchronize(sg));
         if (sh != sg) TG_HIP(hipStreamSynchronize(sh));
+        if (dual) TG_HIP(hipStreamSynchronize(sh2));
         if (g_profiling) {
             float ms = 0.f;
             if (!copies.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
@@ -998,6 +1033,7 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
             // nothing of this call may still be running when the tables are reused
             (void)hipStreamSynchronize(sg);
             if (sh != sg) (void)hipStreamSynchronize(sh);
+            if (dual) (void)hipStreamSynchronize(sh2);
             (void)hipGetLastError();
             // evicted tensors may have been overwritten and moved ones have moved:
             // record that much, so that the mapping describes the pool's bytes

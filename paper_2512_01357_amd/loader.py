@@ -157,9 +157,57 @@ def concurrent_stream_pair(device: torch.device, candidates: int = 6):
                 break
         if found:
             break
-    del a, b, c, h
+    del a, b, c
     _STREAM_PAIR[key] = best
+    _SECOND_H2D[key] = _pick_second_transfer_stream(device, best, [x for x in streams if x not in best], h)
+    del h
     return best
+
+
+_SECOND_H2D = {}
+
+
+def _pick_second_transfer_stream(device, pair, others, pinned):
+    """A third stream whose host-to-device copies run beside those of pair[1]
+    (while a kernel runs on pair[0]), or None.  A copy takes about 10 us to
+    start on its stream; dealt over two streams that cost disappears -- if the
+    two really are independent queues, which only a measurement shows."""
+    gather, h2d = pair
+    piece = 4 << 20
+    n = pinned.numel() // piece
+    dst = torch.empty(pinned.numel(), dtype=torch.uint8, device=device)
+    a = torch.empty(512 << 20, dtype=torch.uint8, device=device)
+    b = torch.empty(512 << 20, dtype=torch.uint8, device=device)
+
+    def run(second):
+        torch.cuda.synchronize(device)
+        t0 = time.perf_counter()
+        with torch.cuda.stream(gather):
+            for _ in range(4):
+                b.copy_(a, non_blocking=True)
+        for k in range(n):
+            st = second if (second is not None and k & 1) else h2d
+            with torch.cuda.stream(st):
+                dst[k * piece:(k + 1) * piece].copy_(pinned[k * piece:(k + 1) * piece], non_blocking=True)
+        torch.cuda.synchronize(device)
+        return time.perf_counter() - t0
+
+    run(None)
+    alone = min(run(None) for _ in range(3))
+    best, best_t = None, 0.96 * alone
+    for st in others:
+        t = min(run(st) for _ in range(3))
+        if t < best_t:
+            best, best_t = st, t
+    del dst, a, b
+    return best
+
+
+def second_transfer_stream(device: torch.device):
+    """The stream chosen by concurrent_stream_pair's measurement for the second
+    half of the host-to-device copies, or None if none helped."""
+    concurrent_stream_pair(device)
+    return _SECOND_H2D.get(str(device))
 
 
 class ReusePool:
@@ -173,6 +221,7 @@ class ReusePool:
         if self.slab.data_ptr() % align:
             raise RuntimeError("slab is not aligned to %d" % align)
         self.stream_gather, self.stream_h2d = concurrent_stream_pair(self.device)
+        self.stream_h2d_second = second_transfer_stream(self.device)
         self.pool = tg.tg_pool_create(self.slab.data_ptr(), capacity, align)
         self.base = self.slab.data_ptr()
 
@@ -203,9 +252,10 @@ class ReusePool:
             info = tg.tg_plan_info(plan)
             info.update({"ops": rows, "moves": tg.tg_plan_moves(plan),
                          "evictions": tg.tg_plan_evictions(plan)})
-            ptrs = tg.tg_assemble(self.pool, plan, model.desc.n,
-                                  tg.TG_ASSEMBLE_VERIFY if verify else 0,
-                                  self.stream_gather, self.stream_h2d)
+            ptrs = tg.tg_assemble_ex(self.pool, plan, model.desc.n,
+                                     tg.TG_ASSEMBLE_VERIFY if verify else 0,
+                                     self.stream_gather, self.stream_h2d, self.stream_h2d_second,
+                                     use_second_h2d_stream=self.stream_h2d_second is not None)
         finally:
             tg.tg_plan_free(plan)
         return ptrs, info

@@ -72,6 +72,12 @@ class tg_entry(ctypes.Structure):
                 ("n_owners", ctypes.c_uint32), ("active_refs", ctypes.c_uint32)]
 
 
+class tg_assemble_args(ctypes.Structure):
+    _fields_ = [("flags", ctypes.c_uint32), ("use_second_h2d_stream", ctypes.c_uint32),
+                ("stream_gather", ctypes.c_void_p), ("stream_h2d", ctypes.c_void_p),
+                ("stream_h2d_second", ctypes.c_void_p)]
+
+
 class tg_move(ctypes.Structure):
     _fields_ = [("old_off", ctypes.c_uint64), ("new_off", ctypes.c_uint64), ("nbytes", ctypes.c_uint64)]
 
@@ -110,7 +116,7 @@ _lib = None
 EXPORTS = [
     "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_pool_regions", "tg_pool_entries", "tg_fingerprint", "tg_compare",
     "tg_plan", "tg_plan_ops", "tg_plan_info", "tg_plan_moves", "tg_plan_evictions", "tg_plan_free",
-    "tg_assemble", "tg_commit", "tg_abandon", "tg_release", "tg_set_model_cost", "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
+    "tg_assemble", "tg_assemble_ex", "tg_commit", "tg_abandon", "tg_release", "tg_set_model_cost", "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
     "tg_host_alloc", "tg_host_free", "tg_shutdown", "tg_strerror",
 ]
 
@@ -142,6 +148,7 @@ def lib() -> ctypes.CDLL:
             "tg_set_model_cost": ([vp, u64, ctypes.c_double, ctypes.c_double, ctypes.c_double], i32),
             "tg_plan_free": ([vp], None),
             "tg_assemble": ([vp, vp, u32, vp, vp, P(vp)], i32),
+            "tg_assemble_ex": ([vp, vp, P(tg_assemble_args), P(vp)], i32),
             "tg_commit": ([vp, vp, P(vp)], i32),
             "tg_abandon": ([vp, vp], i32),
             "tg_release": ([vp, u64, u32], i32),
@@ -318,6 +325,15 @@ def tg_assemble(pool, plan, n_tensors: int, flags: int = 0, stream_gather=None,
     out = (ctypes.c_void_p * max(n_tensors, 1))()
     _check(lib().tg_assemble(pool, plan, flags, _stream(stream_gather), _stream(stream_h2d), out),
            "tg_assemble")
+    return [int(out[k] or 0) for k in range(n_tensors)]
+
+
+def tg_assemble_ex(pool, plan, n_tensors: int, flags: int = 0, stream_gather=None, stream_h2d=None,
+                   stream_h2d_second=None, use_second_h2d_stream: bool = False) -> List[int]:
+    out = (ctypes.c_void_p * max(n_tensors, 1))()
+    args = tg_assemble_args(flags, 1 if use_second_h2d_stream else 0, _stream(stream_gather),
+                            _stream(stream_h2d), _stream(stream_h2d_second))
+    _check(lib().tg_assemble_ex(pool, plan, ctypes.byref(args), out), "tg_assemble_ex")
     return [int(out[k] or 0) for k in range(n_tensors)]
 
 

@@ -211,15 +211,19 @@ def test_a_moved_tensor_that_no_longer_matches_its_row_is_dropped():
     b.close()
 
 
-@pytest.mark.parametrize("streams", ["one side stream", "null stream", "null + side", "side + null"])
+@pytest.mark.parametrize("streams", ["one side stream", "null stream", "null + side", "side + null",
+                                     "three side streams", "second = first", "second = gather", "null + two side"])
 def test_moves_gather_and_transfer_on_any_pair_of_streams(streams):
     say("merge + gather + transfer on %s, with a transfer large enough for the pipelined verification" % streams)
     rnd = random.Random(5)
     b = Both(600 * MIB)
     side = b.pool.stream_gather
-    b.pool.stream_gather, b.pool.stream_h2d = {
-        "one side stream": (side, side), "null stream": (None, None),
-        "null + side": (None, side), "side + null": (side, None)}[streams]
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    b.pool.stream_gather, b.pool.stream_h2d, b.pool.stream_h2d_second = {
+        "one side stream": (side, side, None), "null stream": (None, None, None),
+        "null + side": (None, side, None), "side + null": (side, None, None),
+        "three side streams": (side, s1, s2), "second = first": (side, s1, s1),
+        "second = gather": (side, s1, side), "null + two side": (None, s1, s2)}[streams]
     # F8 A40 F8 B24 F(rest): residents A and B are also tensors of the incoming model (gathered);
     # the 300 MiB miss (pipelined verification: batches of >= 64 MiB) leaves room only if A, B merge
     carve(b, rnd, [(8, False), (40, True), (8, False), (24, True), (8, False)], MIB)
