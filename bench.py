@@ -191,6 +191,9 @@ def main():
             r.materialise(name)
     st0 = r.pool.stats()
     log("pool before loads: %s" % st0)
+    from paper_2512_01357_amd.loader import SECOND_H2D_MEASUREMENT
+    log("host-to-device copies on %s (32 x 4 MiB beside a device copy: %s)"
+        % ("two streams" if r.pool.stream_h2d_second is not None else "one stream", SECOND_H2D_MEASUREMENT.get("cuda:0")))
 
     if args.pmc_calibration:
         a = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda:0")
@@ -319,6 +322,7 @@ def main():
                    "designated_shared_tensors": sum(w.designated_shared.values()) // max(1, len(w.designated_shared)),
                    "verify_fingerprint": verify,
                    "plan_flags": sorted(k for k, v in w.load_flags.items() if v),
+                   "h2d_streams": 2 if r.pool.stream_h2d_second is not None else 1,
                    "model_cache": ("streamed in %d parts (pinned host memory is capped below the model size); "
                                    "only the loads are timed" % len(names)) if w.streamed else "whole model pinned"},
         "fingerprint_GBps": round(fp_gbps, 1),

@@ -165,6 +165,7 @@ def concurrent_stream_pair(device: torch.device, candidates: int = 6):
 
 
 _SECOND_H2D = {}
+SECOND_H2D_MEASUREMENT = {}          # what the choice was based on, per device (for logs)
 
 
 def _pick_second_transfer_stream(device, pair, others, pinned):
@@ -195,10 +196,13 @@ def _pick_second_transfer_stream(device, pair, others, pinned):
     run(None)
     alone = min(run(None) for _ in range(3))
     best, best_t = None, 0.96 * alone
+    tried = []
     for st in others:
         t = min(run(st) for _ in range(3))
+        tried.append(round(t * 1e3, 3))
         if t < best_t:
             best, best_t = st, t
+    SECOND_H2D_MEASUREMENT[str(device)] = {"one_stream_ms": round(alone * 1e3, 3), "two_streams_ms": tried}
     del dst, a, b
     return best
 
