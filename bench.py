@@ -217,7 +217,7 @@ def main():
             reg = r.materialise(name)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            ptrs, info = r.load(name, verify=verify)
+            ptrs, info = r.load(name, verify=verify, details=False)
             torch.cuda.synchronize()
             timed = time.perf_counter() - t0
             t = tg.tg_last_timing()
@@ -225,7 +225,7 @@ def main():
             return [(name, info, t, reg.nbytes)], timed
         if not w.streamed:
             name = names[i % len(names)]
-            ptrs, info = r.load(name, verify=verify)
+            ptrs, info = r.load(name, verify=verify, details=False)
             t = tg.tg_last_timing()
             r.release(name, True)
             return [(name, info, t, r.models[name].nbytes)], None
@@ -236,7 +236,7 @@ def main():
             reg = r.materialise(name)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            ptrs, info = r.load(name, verify=verify)
+            ptrs, info = r.load(name, verify=verify, details=False)
             torch.cuda.synchronize()
             timed += time.perf_counter() - t0
             out.append((name, info, tg.tg_last_timing(), reg.nbytes))
@@ -318,7 +318,7 @@ def main():
                    "tensors": sum(len(w.models[n].tensors) for n in (names if w.streamed else names[:1])),
                    "pool_bytes": w.pool_bytes,
                    "reused_fraction": round(sum(rec[1]["reused_bytes"] for rec in recs) / total_bytes, 4),
-                   "reused_tensors": int(sum(sum(1 for op in rec[1]["ops"] if op[0] == 0) for rec in recs) / args.steps),
+                   "reused_tensors": int(sum(rec[1]["n_reused"] for rec in recs) / args.steps),
                    "designated_shared_tensors": sum(w.designated_shared.values()) // max(1, len(w.designated_shared)),
                    "verify_fingerprint": verify,
                    "plan_flags": sorted(k for k, v in w.load_flags.items() if v),

@@ -132,6 +132,8 @@ typedef struct {
     uint32_t n_evictions;     /* tensors Stage 1 evicts */
     uint32_t n_moves;         /* tensors Stage 2 moves */
     uint32_t alias;           /* 1 if the plan was made with TG_PLAN_ALIAS */
+    uint32_t n_reused;        /* tensors found resident (rows of kind TG_OP_REUSE) */
+    uint32_t reserved;
     uint64_t reused_bytes;    /* bytes found resident */
     uint64_t transfer_bytes;  /* bytes that come from the host */
     uint64_t copy_bytes;      /* bytes the gather kernel copies (0 in alias mode) */

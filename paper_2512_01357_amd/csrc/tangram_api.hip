@@ -606,6 +606,9 @@ tg_status tg_plan_info(const tg_load_plan *plan, tg_plan_summary *out) {
     out->n_evictions = uint32_t(p.evict.size());
     out->n_moves = uint32_t(p.moves.size());
     out->alias = p.alias ? 1u : 0u;
+    out->n_reused = 0;
+    for (const tg::Op &op : p.ops) out->n_reused += op.kind == 0 ? 1u : 0u;
+    out->reserved = 0;
     out->reused_bytes = p.reused_bytes;
     out->transfer_bytes = p.transfer_bytes;
     out->copy_bytes = p.copy_bytes;

@@ -245,17 +245,19 @@ class ReusePool:
 
     def load(self, model: RegisteredModel, confirm: bool = False, verify: bool = False,
              evict: bool = False, merge: bool = False, alias: bool = False,
-             pack_text: bool = False) -> Tuple[List[int], dict]:
-        """tg_plan + tg_assemble.  Returns device addresses and what the plan held."""
+             pack_text: bool = False, details: bool = True) -> Tuple[List[int], dict]:
+        """tg_plan + tg_assemble.  Returns device addresses and what the plan held
+        (with details=False only its totals: no per-tensor rows are fetched)."""
         flags = ((tg.TG_PLAN_CONFIRM if confirm else 0) | (tg.TG_PLAN_EVICT if evict else 0)
                  | (tg.TG_PLAN_MERGE if merge else 0) | (tg.TG_PLAN_ALIAS if alias else 0)
                  | (tg.TG_PLAN_PACK_TEXT if pack_text else 0))
         plan = tg.tg_plan(self.pool, model.desc, flags, self.stream_gather)
         try:
-            rows, reused, transfer = tg.tg_plan_ops(plan)
             info = tg.tg_plan_info(plan)
-            info.update({"ops": rows, "moves": tg.tg_plan_moves(plan),
-                         "evictions": tg.tg_plan_evictions(plan)})
+            if details:
+                rows, _reused, _transfer = tg.tg_plan_ops(plan)
+                info.update({"ops": rows, "moves": tg.tg_plan_moves(plan),
+                             "evictions": tg.tg_plan_evictions(plan)})
             ptrs = tg.tg_assemble_ex(self.pool, plan, model.desc.n,
                                      tg.TG_ASSEMBLE_VERIFY if verify else 0,
                                      self.stream_gather, self.stream_h2d, self.stream_h2d_second,

@@ -111,12 +111,12 @@ class WorkloadRunner:
         for name, (p, b, a) in self.w.costs.items():
             self.pool.set_model_cost(self.w.models[name].model_id, p, b, a)
 
-    def load(self, name: str, confirm: bool = False, verify: bool = False, **flags):
+    def load(self, name: str, confirm: bool = False, verify: bool = False, details: bool = True, **flags):
         """Loads a model; plan flags default to the workload's for its measured loads."""
         reg = self.materialise(name)
         if not flags and name in self.w.loads:
             flags = dict(self.w.load_flags)
-        return self.pool.load(reg, confirm=confirm, verify=verify, **flags)
+        return self.pool.load(reg, confirm=confirm, verify=verify, details=details, **flags)
 
     def reset_pool(self) -> None:
         """Evict everything and replay the setup (for workloads whose measured

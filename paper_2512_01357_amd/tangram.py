@@ -83,7 +83,8 @@ class tg_move(ctypes.Structure):
 
 
 class tg_plan_summary(ctypes.Structure):
-    _fields_ = ([(n, ctypes.c_uint32) for n in ("n_tensors", "n_evictions", "n_moves", "alias")]
+    _fields_ = ([(n, ctypes.c_uint32) for n in ("n_tensors", "n_evictions", "n_moves", "alias", "n_reused",
+                                                "reserved")]
                 + [(n, ctypes.c_uint64) for n in (
                     "reused_bytes", "transfer_bytes", "copy_bytes", "evicted_bytes", "moved_bytes",
                     "merge_bound")])

@@ -53,6 +53,7 @@ int main(void) {
     CHECK(ops[0].kind == TG_OP_REUSE && ops[0].dst_off == 0 && ops[0].src_off == 0);
     tg_plan_summary info;
     CHECK(tg_plan_info(plan, &info) == TG_OK && info.alias == 1 && info.copy_bytes == 0 && info.n_moves == 0);
+    CHECK(info.n_reused == 1 && info.n_tensors == 2);
     CHECK(tg_commit(pool, plan, ptrs) == TG_OK && ptrs[0] == base);
     tg_plan_free(plan);
 
