@@ -807,15 +807,16 @@ tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_ar
     const u64 tile = tile_for(tgk::kCopyThreads, U);
     const u32 FU = pick_u(g_tune.fingerprint_unroll);
     const u64 fp_tile = tile_for(tgk::kReadThreads, FU);
-    struct Placed { size_t desc_off, prefix_off; u32 n, tiles; };
+    struct Placed { size_t desc_off, prefix_off, ticket_off; u32 n, tiles; };
     std::vector<Placed> placed(launches.size());
     size_t table_bytes = 0;
     for (size_t i = 0; i < launches.size(); ++i) {
         const TableLayout L = table_layout(launches[i].size(), sizeof(tgk::Copy), 0);
         placed[i].desc_off = table_bytes + L.desc_off;
         placed[i].prefix_off = table_bytes + L.prefix_off;
+        placed[i].ticket_off = table_bytes + L.total;    // the launch's tile counter, uploaded as zero
         placed[i].n = u32(launches[i].size());
-        table_bytes += L.total;
+        table_bytes += L.total + 256;
     }
     size_t results_off = 0, results_words = 0;
     if (verify) {
@@ -844,6 +845,7 @@ tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_ar
             if (!fill_prefix(hp, &launches[i][0].nbytes, sizeof(tgk::Copy) / 8, launches[i].size(), tile))
                 return TG_ERR_INVALID;
             placed[i].tiles = hp[launches[i].size()];
+            std::memset(h + placed[i].ticket_off, 0, 256);
         }
         if (verify) {
             for (FpGroup &g : groups) {
@@ -873,10 +875,10 @@ tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_ar
         if (placed[i].tiles == 0) return TG_OK;
         char *d = static_cast<char *>(g_scratch.d);
         const u32 grid = grid_for(placed[i].tiles, g_tune.gather_wgs_per_cu);
-        const u32 run = run_for(placed[i].tiles, grid);
         TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU><<<dim3(grid), dim3(tgk::kCopyThreads), 0, sg>>>(
                         reinterpret_cast<const tgk::Copy *>(d + placed[i].desc_off),
-                        reinterpret_cast<const u32 *>(d + placed[i].prefix_off), placed[i].n, run));
+                        reinterpret_cast<const u32 *>(d + placed[i].prefix_off), placed[i].n,
+                        reinterpret_cast<u32 *>(d + placed[i].ticket_off)));
         TG_HIP(hipGetLastError());
         return TG_OK;
     };
