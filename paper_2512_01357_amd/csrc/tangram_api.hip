@@ -26,7 +26,7 @@ using tgk::u64;
 
 // Loads in flight per lane (U) and resident workgroups per compute unit for
 // each kernel.  Chosen by measurement on MI355X; see tg_set_tuning.
-tg_tuning g_tune = {4, 2, 8, 1, 4, 2, uint64_t(64) << 10};
+tg_tuning g_tune = {8, 4, 4, 1, 4, 2, uint64_t(64) << 10};
 
 bool g_profiling = false;
 tg_timing g_timing = {};

@@ -283,7 +283,7 @@ class Both:
         self.pool.close()
 
 
-@pytest.mark.parametrize("gather_unroll", [2, 8, 16])
+@pytest.mark.parametrize("gather_unroll", [2, 4, 8, 16])
 def test_load_small_models_ragged_sizes(gather_unroll):
     say("assemble ragged sizes gather_unroll=%d" % gather_unroll)
     old = tg.tg_get_tuning()
