@@ -12,11 +12,11 @@
 //
 // Measured on MI355X (13.5 GB, 291 extents): dealing tiles round-robin
 // instead costs a quarter of the fingerprint's bandwidth (a descriptor fetch
-// and a cross-wave fold at almost every tile), and two workgroups of 256 lanes
-// per compute unit read faster than more.  The copy does best with 1024-lane
-// workgroups that read 128 KiB, meet at a barrier, then write 128 KiB: keeping
-// a compute unit's reads and writes in separate bursts is worth ~10 %, and
-// handing the tiles out dynamically another 12 %.
+// and a cross-wave fold at almost every tile); two to four workgroups of 256
+// lanes per compute unit read equally fast, one starves.  The copy does best
+// with 1024-lane workgroups that read a 64 KiB tile, meet at a barrier, then
+// write it: keeping a compute unit's reads and writes in separate bursts is
+// worth ~10 %, and handing the tiles out dynamically another 12-17 %.
 //
 // None of this is a dense contraction, so there is no MFMA here; nothing is
 // reused across tiles, so the only data kept in LDS is the per-wave partial
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(T) void compare_kernel(const Pair *__restrict__ pai
 // before the launch): a workgroup that is done takes the next tile, whichever
 // extent it belongs to.  Workgroups do not run at the same pace -- with equal
 // contiguous runs the fast ones wait for the slow ones at the end, which costs
-// a copy 12 % on MI355X (5.93 against 6.65 TB/s over 7 GiB).  The next ticket
+// a copy 12-17 % on MI355X (5.93 against 6.65-6.97 TB/s over 7 GiB).  The next ticket
 // is drawn while the current tile is being stored.  Unlike the fingerprint, a
 // copy carries nothing from tile to tile, so changing extent costs one table
 // look-up.
