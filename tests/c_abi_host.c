@@ -54,8 +54,32 @@ int main(void) {
     tg_plan_summary info;
     CHECK(tg_plan_info(plan, &info) == TG_OK && info.alias == 1 && info.copy_bytes == 0 && info.n_moves == 0);
     CHECK(info.n_reused == 1 && info.n_tensors == 2);
+    {   /* argument checks of the extended assemble come before anything touches the device */
+        tg_assemble_args args;
+        memset(&args, 0, sizeof args);
+        CHECK(tg_assemble_ex(pool, plan, NULL, ptrs) == TG_ERR_INVALID);
+        args.flags = 8u;
+        CHECK(tg_assemble_ex(pool, plan, &args, ptrs) == TG_ERR_INVALID);
+        CHECK(tg_assemble_ex(NULL, plan, &args, ptrs) == TG_ERR_INVALID);
+    }
     CHECK(tg_commit(pool, plan, ptrs) == TG_OK && ptrs[0] == base);
     tg_plan_free(plan);
+
+    /* the Region List and the Tensor Mapping can be read out */
+    {
+        tg_region regs[8];
+        tg_entry rows[8];
+        uint32_t nr = 0, ne = 0;
+        CHECK(tg_pool_regions(pool, NULL, 0, &nr) == TG_OK && nr == 4);
+        CHECK(tg_pool_regions(pool, regs, 8, &nr) == TG_OK && nr == 4);
+        CHECK(regs[0].off == 0 && regs[0].len == 768 && regs[0].free == 0);
+        CHECK(regs[3].free == 1 && regs[3].off + regs[3].len == 4096);
+        CHECK(tg_pool_entries(pool, rows, 8, &ne) == TG_OK && ne == 3);
+        CHECK(rows[0].off == 0 && rows[0].nbytes == 700 && rows[0].fp == 0x1111 && rows[0].n_owners == 2 &&
+              rows[0].active_refs == 1);
+        CHECK(tg_pool_entries(pool, rows, 1, &ne) == TG_OK && ne == 3);
+        CHECK(tg_pool_entries(pool, NULL, 1, &ne) == TG_ERR_INVALID);
+    }
 
     /* too big for what is left, and flags nobody defined */
     tg_tensor_desc c[1] = {{4096, 0x4444, 0}};
