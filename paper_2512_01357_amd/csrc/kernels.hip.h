@@ -19,8 +19,8 @@
 // worth ~10 %, and handing the tiles out dynamically another 12-17 %.
 //
 // None of this is a dense contraction, so there is no MFMA here; nothing is
-// reused across tiles, so the only data kept in LDS is the per-wave partial
-// sum of the fingerprint's cross-wave combine.  The XCD a workgroup lands on
+// reused across tiles, so the only data kept in LDS are the per-wave partial
+// sums of the fingerprint's cross-wave combine and the gather's ticket.  The XCD a workgroup lands on
 // does not matter for correctness or reuse (each byte is touched once); the
 // descriptor tables are a few KiB and end up in every XCD's L2.
 #pragma once
@@ -278,10 +278,11 @@ __global__ __launch_bounds__(T) void compare_kernel(const Pair *__restrict__ pai
 // before the launch): a workgroup that is done takes the next tile, whichever
 // extent it belongs to.  Workgroups do not run at the same pace -- with equal
 // contiguous runs the fast ones wait for the slow ones at the end, which costs
-// a copy 12-17 % on MI355X (5.93 against 6.65-6.97 TB/s over 7 GiB).  The next ticket
-// is drawn while the current tile is being stored.  Unlike the fingerprint, a
-// copy carries nothing from tile to tile, so changing extent costs one table
-// look-up.
+// a copy 12-17 % on MI355X (5.93 against 6.65-6.97 TB/s over 7 GiB).  The
+// ticket is drawn at the top of the loop and waited for; drawing the next one
+// while the current tile is being stored measured 2 % slower.  Unlike the
+// fingerprint, a copy carries nothing from tile to tile, so changing extent
+// costs one table look-up.
 template <int T, int U>
 __global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copies,
                                                     const u32 *__restrict__ prefix, u32 n_copies,
@@ -290,10 +291,11 @@ __global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copi
     __shared__ u32 next_tile;
     const u32 tid = threadIdx.x;
     const u32 total = prefix[n_copies];
-    if (tid == 0) next_tile = atomicAdd(ticket, 1u);
-    __syncthreads();
     for (;;) {
+        if (tid == 0) next_tile = atomicAdd(ticket, 1u);
+        __syncthreads();
         const u32 t = __builtin_amdgcn_readfirstlane(next_tile);
+        __syncthreads();                           // every lane has read next_tile
         if (t >= total) return;                    // workgroup-uniform
         const u32 s = locate_first(prefix, n_copies, t);
         const Copy cp = copies[s];
@@ -305,8 +307,7 @@ __global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copi
             u32x4 v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) v[u] = load16(ps + (u64(u) * T + tid) * 16);
-            __syncthreads();                       // every lane has read next_tile
-            if (tid == 0) next_tile = atomicAdd(ticket, 1u);
+            __syncthreads();
 #pragma unroll
             for (int u = 0; u < U; ++u) store16(pd + (u64(u) * T + tid) * 16, v[u]);
             __syncthreads();
@@ -315,9 +316,6 @@ __global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copi
             for (u64 i = tid; i < nvec; i += T) store16(pd + i * 16, load16(ps + i * 16));
             const u32 rem = u32(left % 16);
             if (tid < rem) store1(pd + nvec * 16 + tid, load1(ps + nvec * 16 + tid));
-            __syncthreads();
-            if (tid == 0) next_tile = atomicAdd(ticket, 1u);
-            __syncthreads();
         }
     }
 }
