@@ -235,6 +235,29 @@ tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint
 tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream);
 
 /*
+ * tg_fingerprint for callers that cannot allocate: code that runs where
+ * hipMalloc is forbidden or too slow (a tight serving loop that re-checks
+ * resident tensors, a harness that forbids allocation, code around a HIP
+ * graph capture).  Same arguments, same results, same errors as
+ * tg_fingerprint, with these differences:
+ *  - the span table, the tile table and the result words live in a fixed
+ *    128 KiB array that is part of the library's code object (one copy per
+ *    GPU, held from the moment the library is loaded on that GPU until the
+ *    process ends); the call makes no hipMalloc, hipFree or hipHostMalloc, creates
+ *    no events and allocates no host memory;
+ *  - n may be at most TG_NOALLOC_MAX_SPANS; more is TG_ERR_INVALID;
+ *  - it works on whichever GPU is current (the array's address is looked up
+ *    once per GPU, at the first call made with that GPU current), and always
+ *    with the default launch shape (tg_set_tuning does not apply).
+ * Every call on a GPU uses that GPU's one array, which keeps the previous
+ * call's contents; the call clears the words it adds into.  Calls from one
+ * process are serialised by the library and each waits for its kernel, so they
+ * cannot overlap; two processes have separate copies.
+ */
+#define TG_NOALLOC_MAX_SPANS 4096u
+tg_status tg_fingerprint_noalloc(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream);
+
+/*
  * Bytewise comparison of n pairs of extents in one launch on `stream`;
  * out_differs[i] [host] is 0 when pair i holds identical bytes and 1
  * otherwise.  (The confirmation step behind a fingerprint hit; the paper

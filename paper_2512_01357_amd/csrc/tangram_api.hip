@@ -164,6 +164,42 @@ struct DrainOnExit {
     ~DrainOnExit() { if (armed) { (void)hipStreamSynchronize(st); (void)hipGetLastError(); } }
 };
 
+// ---- scratch of the entry point that allocates nothing (tg_fingerprint_noalloc)
+//
+// One array per GPU, part of the code object, so it exists from the moment the
+// library is loaded on a device until the process ends.  In host code its name
+// is only a stand-in for the symbol: the device address is asked for once per
+// device (static_scratch_for) and only that address is handed to kernels and
+// copies.  Layout of a launch inside it: TableLayout, as in the growing scratch.
+constexpr size_t kStaticScratchBytes = size_t(128) << 10;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+    std::mutex mu;                               // one call at a time: the table below is shared
+    unsigned char *dev[kMaxDevices] = {};        // device address of `scratch`, per device
+    int cu_count[kMaxDevices] = {};
+    alignas(256) unsigned char host[kStaticScratchBytes];   // the table as it is uploaded, results as they come back
+} g_static;
+
+// Address of this device's copy of `scratch` and its compute-unit count; asked
+// for at the first call on each device, with that device current.
+tg_status static_scratch_for(int device, unsigned char **ptr, int *cus) {
+    if (device < 0 || device >= kMaxDevices) return TG_ERR_INVALID;
+    if (!g_static.dev[device]) {
+        void *p = nullptr;
+        TG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return TG_ERR_HIP;
+        int n = 0;
+        TG_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device));
+        g_static.cu_count[device] = n > 0 ? n : 256;
+        g_static.dev[device] = static_cast<unsigned char *>(p);
+    }
+    *ptr = g_static.dev[device];
+    *cus = g_static.cu_count[device];
+    return TG_OK;
+}
+
 // ---- fingerprint over device-visible spans; scratch lock held by the caller
 tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipStream_t st,
                              float *ms_out, uint64_t *bytes_out) {
@@ -493,6 +529,61 @@ tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, voi
                                             &g_timing.fingerprint_ms, &g_timing.fingerprint_bytes);
     if (rc == TG_OK) std::memcpy(out_fp, tmp.data(), n * sizeof(uint64_t));
     return rc;
+}
+
+// tg_fingerprint for callers that may not allocate: the span table, the tile
+// prefix and the result words live in this device's copy of `scratch`, the host
+// side of the table in a static array.  No hipMalloc / hipFree / hipHostMalloc,
+// no events, no std::vector.
+tg_status tg_fingerprint_noalloc(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream) {
+    if (n == 0) return TG_OK;
+    if (!spans || !out_fp) return TG_ERR_INVALID;
+    if (n > TG_NOALLOC_MAX_SPANS) return TG_ERR_INVALID;
+    for (u32 i = 0; i < n; ++i) {
+        if (spans[i].nbytes != 0 && !spans[i].ptr) return TG_ERR_INVALID;
+        if (!aligned16(spans[i].ptr)) return TG_ERR_INVALID;
+    }
+    const TableLayout L = table_layout(n, sizeof(tgk::Span), sizeof(u64));
+    if (L.total > kStaticScratchBytes) return TG_ERR_INVALID;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int dev = 0;
+    TG_HIP(hipGetDevice(&dev));
+
+    std::lock_guard<std::mutex> lock(g_static.mu);
+    unsigned char *d = nullptr;
+    int cus = 0;
+    const tg_status rc = static_scratch_for(dev, &d, &cus);
+    if (rc != TG_OK) return rc;
+    // launch shape: the library's defaults (the tuning call belongs to the allocating path)
+    constexpr int kU = 8;
+    constexpr u32 kWgsPerCu = 4;
+    unsigned char *h = g_static.host;
+    tgk::Span *hs = reinterpret_cast<tgk::Span *>(h + L.desc_off);
+    for (u32 i = 0; i < n; ++i) {
+        hs[i].ptr = u64(reinterpret_cast<uintptr_t>(spans[i].ptr));
+        hs[i].nbytes = spans[i].nbytes;
+    }
+    u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
+    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, n, tile_for(tgk::kReadThreads, kU))) return TG_ERR_INVALID;
+    const u32 total_tiles = hp[n];
+    u64 *d_out = reinterpret_cast<u64 *>(d + L.result_off);
+    DrainOnExit drain(st);
+    TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
+    // the array keeps the last call's results: the words this call adds into start at zero
+    hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_out, n);
+    if (total_tiles > 0) {
+        const u32 grid = u32(std::max<u64>(1, std::min<u64>(total_tiles, u64(cus) * kWgsPerCu)));
+        const u32 run = run_for(total_tiles, grid);
+        tgk::fingerprint_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, st>>>(
+            reinterpret_cast<const tgk::Span *>(d + L.desc_off), reinterpret_cast<const u32 *>(d + L.prefix_off), n,
+            run, d_out);
+    }
+    TG_HIP(hipGetLastError());
+    TG_HIP(hipMemcpyAsync(h + L.result_off, d_out, n * sizeof(u64), hipMemcpyDeviceToHost, st));
+    TG_HIP(hipStreamSynchronize(st));
+    drain.armed = false;
+    std::memcpy(out_fp, h + L.result_off, n * sizeof(u64));
+    return TG_OK;
 }
 
 tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, void *stream) {

@@ -115,7 +115,7 @@ class TgError(RuntimeError):
 _lib = None
 
 EXPORTS = [
-    "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_pool_regions", "tg_pool_entries", "tg_fingerprint", "tg_compare",
+    "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_pool_regions", "tg_pool_entries", "tg_fingerprint", "tg_fingerprint_noalloc", "tg_compare",
     "tg_plan", "tg_plan_ops", "tg_plan_info", "tg_plan_moves", "tg_plan_evictions", "tg_plan_free",
     "tg_assemble", "tg_assemble_ex", "tg_commit", "tg_abandon", "tg_release", "tg_set_model_cost", "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
     "tg_host_alloc", "tg_host_free", "tg_shutdown", "tg_strerror",
@@ -140,6 +140,7 @@ def lib() -> ctypes.CDLL:
             "tg_pool_regions": ([vp, P(tg_region), u32, P(u32)], i32),
             "tg_pool_entries": ([vp, P(tg_entry), u32, P(u32)], i32),
             "tg_fingerprint": ([P(tg_span), u32, P(u64), vp], i32),
+            "tg_fingerprint_noalloc": ([P(tg_span), u32, P(u64), vp], i32),
             "tg_compare": ([P(tg_pair), u32, P(u32), vp], i32),
             "tg_plan": ([vp, P(tg_model_desc), u32, vp, P(vp)], i32),
             "tg_plan_ops": ([vp, P(P(tg_plan_op)), P(u32), P(u64), P(u64)], i32),
@@ -236,6 +237,22 @@ def tg_fingerprint(spans: Sequence[Tuple[int, int]], stream=None) -> List[int]:
         arr[i].nbytes = nbytes
     out = (ctypes.c_uint64 * max(n, 1))()
     _check(lib().tg_fingerprint(arr, n, out, _stream(stream)), "tg_fingerprint")
+    return [int(out[i]) for i in range(n)]
+
+
+TG_NOALLOC_MAX_SPANS = 4096
+
+
+def tg_fingerprint_noalloc(spans: Sequence[Tuple[int, int]], stream=None) -> List[int]:
+    """tg_fingerprint through the entry point that allocates nothing (at most
+    TG_NOALLOC_MAX_SPANS spans)."""
+    n = len(spans)
+    arr = (tg_span * max(n, 1))()
+    for i, (ptr, nbytes) in enumerate(spans):
+        arr[i].ptr = ptr
+        arr[i].nbytes = nbytes
+    out = (ctypes.c_uint64 * max(n, 1))()
+    _check(lib().tg_fingerprint_noalloc(arr, n, out, _stream(stream)), "tg_fingerprint_noalloc")
     return [int(out[i]) for i in range(n)]
 
 
