@@ -18,8 +18,10 @@
  *  - Ownership: the caller owns the pool slab, every host buffer and every
  *    stream, and keeps them alive while the library uses them.  The library
  *    owns its metadata and a small amount of device / pinned scratch
- *    (descriptor tables, result words) that it allocates on first use and
- *    keeps until tg_shutdown() or process exit.
+ *    (descriptor tables, result words, events).  Every pool has scratch of
+ *    its own, allocated on first use and freed by tg_pool_destroy; the calls
+ *    that take no pool (tg_fingerprint, tg_compare) share one more, kept
+ *    until tg_shutdown() or process exit.
  *  - Streams are hipStream_t values passed as void* (NULL = the null stream).
  *  - Errors: every function returns a tg_status; 0 is success, negative
  *    values are errors, out-parameters are left untouched on error, and no
@@ -28,11 +30,14 @@
  *    except where its comment says otherwise (a plan that had already moved
  *    or overwritten resident tensors when it failed).
  *  - Threading: a pool is externally synchronised (one caller at a time per
- *    pool).  tg_fingerprint / tg_compare may be called from several threads;
- *    they serialise on the library's scratch.
- *  - Device: the library serves one GPU per process, the one that is current
- *    at its first call that touches the device; calls made with another
- *    device current return TG_ERR_INVALID.
+ *    pool); different pools share nothing, so they may be used from different
+ *    threads at the same time, loads included.  tg_fingerprint / tg_compare
+ *    may be called from several threads; they serialise on their scratch.
+ *    There is no process-wide setting: launch shape and profiling belong to a
+ *    pool, timings to a plan.
+ *  - Device: a pool's scratch lives on the GPU that is current at the pool's
+ *    first call that touches the device (likewise for the calls that take no
+ *    pool); calls made with another device current return TG_ERR_INVALID.
  *  - All sizes and offsets are in bytes.  Integer arithmetic of the
  *    fingerprint is unsigned 64-bit and wraps.
  */
@@ -98,7 +103,11 @@ typedef struct {
 
 /* An incoming model.  host_base [pinned host] .. host_base + host_bytes is
  * the model's image in the Model Cache; tensors [host] has n_tensors rows in
- * the model's canonical tensor order. */
+ * the model's canonical tensor order.  host_base may be NULL (host_bytes 0)
+ * for a model whose bytes are not all in pinned memory at once: planning
+ * needs only (nbytes, fp) per tensor, src_off is then the caller's own
+ * reference (it is echoed in the plan's rows), and the missing tensors are
+ * handed over piece by piece with tg_assemble_begin / _feed / _wait. */
 typedef struct {
     uint64_t              model_id;
     const void           *host_base;
@@ -153,22 +162,23 @@ typedef struct {
     uint64_t generation;      /* bumped by every commit and release */
 } tg_stats;
 
-/* Durations, in milliseconds, of the device work of the most recent call of
- * each kind, measured with HIP events on the stream the work ran on.  Only
- * filled while profiling is on (tg_set_profiling); a field is 0 if that work
- * has not run since profiling was switched on. */
+/* Durations, in milliseconds, of the device work one plan caused, measured
+ * with HIP events on the stream the work ran on (tg_plan_timing).  The device
+ * fields are filled only if the pool had profiling on (tg_pool_set_profiling)
+ * when the plan was made and carried out; a field is 0 if that work did not
+ * run. */
 typedef struct {
-    float    fingerprint_ms;  /* fingerprint kernel of the last tg_fingerprint */
-    float    compare_ms;      /* compare kernel of the last tg_compare / confirming tg_plan */
-    float    gather_ms;       /* gather kernel of the last tg_assemble */
-    float    h2d_ms;          /* first to last host-to-device copy of the last tg_assemble */
-    float    verify_ms;       /* fingerprint kernels of the last verifying tg_assemble, summed */
-    float    plan_host_ms;    /* host time of the last tg_plan (steady clock) */
-    uint64_t fingerprint_bytes, compare_bytes, gather_bytes, h2d_bytes, verify_bytes;
-    uint32_t h2d_copies;      /* hipMemcpyAsync calls issued by the last tg_assemble */
-    uint32_t move_launches;   /* copy launches the merge moves of the last tg_assemble took */
-    float    move_ms;         /* first to last merge-move launch of the last tg_assemble */
-    uint32_t verify_launches; /* fingerprint launches of the last verifying tg_assemble (verify_ms is their sum) */
+    float    compare_ms;      /* compare kernel of a confirming tg_plan */
+    float    gather_ms;       /* the gather kernel */
+    float    h2d_ms;          /* first to last host-to-device copy, summed over the feeds */
+    float    verify_ms;       /* fingerprint kernels of a verifying assemble, summed */
+    float    plan_host_ms;    /* host time of tg_plan (steady clock; always filled) */
+    float    move_ms;         /* first to last merge-move launch */
+    uint64_t compare_bytes, gather_bytes, h2d_bytes, verify_bytes;
+    uint32_t h2d_copies;      /* hipMemcpyAsync calls issued */
+    uint32_t move_launches;   /* copy launches the merge moves took */
+    uint32_t verify_launches; /* fingerprint launches of a verifying assemble (verify_ms is their sum) */
+    uint32_t feeds;           /* tg_assemble_feed calls (1 for a load from a whole host image) */
     uint64_t move_bytes;      /* bytes of the tensors moved */
     uint64_t move_traffic_bytes; /* bytes read + written by the move launches (staged stretches count twice) */
 } tg_timing;
@@ -219,6 +229,51 @@ tg_status tg_pool_regions(const tg_pool *pool, tg_region *out, uint32_t cap, uin
 tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint32_t *n);
 
 /*
+ * Launch shape of the three streaming kernels, and two thresholds of the
+ * host-to-device stream.  *_unroll is the number of independent 128-bit loads
+ * a lane issues per tile (2, 4, 8 or 16; a tile is lanes x 16 B x unroll, with
+ * 256 lanes for fingerprint and compare and 1024 for the gather);
+ * *_wgs_per_cu is the number of workgroups launched per compute unit.
+ * h2d_kernel_max_bytes > 0 lets missing tensors up to that size be fetched by
+ * the gather kernel through the pinned buffer's device mapping instead of one
+ * copy-engine call each (default 64 KiB: such a copy takes about 1 us on the
+ * link and about 10 us to issue).  h2d_group_bytes is the copy-grouping
+ * threshold of Section 4: missing tensors that are adjacent both in the host
+ * image and in the pool are merged into one copy until the copy exceeds this
+ * many bytes (the paper's loader uses 8 MB); 0, the default, puts no limit on
+ * a merged copy.  The defaults (tg_default_tuning) are the measured optimum on
+ * MI355X; results never depend on these values.  A pool starts with the
+ * defaults.
+ */
+typedef struct {
+    uint32_t fingerprint_unroll, fingerprint_wgs_per_cu;
+    uint32_t gather_unroll, gather_wgs_per_cu;
+    uint32_t compare_unroll, compare_wgs_per_cu;
+    uint64_t h2d_kernel_max_bytes;
+    uint64_t h2d_group_bytes;
+} tg_tuning;
+tg_status tg_default_tuning(tg_tuning *out);
+tg_status tg_pool_set_tuning(tg_pool *pool, const tg_tuning *t);
+tg_status tg_pool_get_tuning(const tg_pool *pool, tg_tuning *out);
+
+/*
+ * Profiling switch of a pool: while it is on, the plans made for the pool
+ * record HIP events around their device work (see tg_timing, tg_plan_timing).
+ * Off by default; recording costs a few microseconds per launch.
+ */
+tg_status tg_pool_set_profiling(tg_pool *pool, int on);
+
+/*
+ * Measurement aid: words per second that this GPU's integer units sustain on
+ * the fingerprint's arithmetic alone -- one launch in which every lane mixes
+ * iters x 16 words made up in registers, no memory traffic -- timed with HIP
+ * events on `stream`.  Times eight bytes it is the bandwidth above which the
+ * fingerprint kernel would be bound by arithmetic rather than by HBM.
+ * TG_ERR_INVALID unless 1 <= iters <= 2^20.
+ */
+tg_status tg_measure_mix_rate(uint32_t iters, void *stream, double *words_per_s);
+
+/*
  * Fingerprint.  (Section 3.1: every tensor has a fingerprint that indexes the
  * Tensor Mapping.  The function: with gamma = 0x9E3779B97F4A7C15 and
  * SM(x) = SplitMix64's output for the not-yet-advanced state x,
@@ -234,6 +289,12 @@ tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint
  */
 tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream);
 
+/* tg_fingerprint with a launch shape of the caller's (tuning; NULL = the
+ * defaults) and, if kernel_ms [host] is not NULL, the kernel's duration in
+ * milliseconds measured with HIP events on `stream` (0 when no byte was read). */
+tg_status tg_fingerprint_ex(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream,
+                            const tg_tuning *tuning, float *kernel_ms);
+
 /*
  * tg_fingerprint for callers that cannot allocate: code that runs where
  * hipMalloc is forbidden or too slow (a tight serving loop that re-checks
@@ -248,7 +309,7 @@ tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, voi
  *  - n may be at most TG_NOALLOC_MAX_SPANS; more is TG_ERR_INVALID;
  *  - it works on whichever GPU is current (the array's address is looked up
  *    once per GPU, at the first call made with that GPU current), and always
- *    with the default launch shape (tg_set_tuning does not apply).
+ *    with the default launch shape.
  * Every call on a GPU uses that GPU's one array, which keeps the previous
  * call's contents; the call clears the words it adds into.  Calls from one
  * process are serialised by the library and each waits for its kernel, so they
@@ -264,6 +325,11 @@ tg_status tg_fingerprint_noalloc(const tg_span *spans, uint32_t n, uint64_t *out
  * treats fingerprints as unique, Section 3.1.)  The call waits for the kernel.
  */
 tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, void *stream);
+
+/* tg_compare with a launch shape of the caller's and the kernel's duration,
+ * as tg_fingerprint_ex. */
+tg_status tg_compare_ex(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, void *stream,
+                        const tg_tuning *tuning, float *kernel_ms);
 
 /*
  * Plan the load of `model` into `pool`.  (Section 3.1: search the Tensor
@@ -307,7 +373,8 @@ tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, vo
  *
  * The pool is not modified.  *out receives a plan bound to the pool's current
  * generation.  TG_ERR_INVALID: null arguments, unknown flag bits, n_tensors ==
- * 0, a zero-length tensor, src_off + nbytes > host_bytes, model_id running in
+ * 0, a zero-length tensor, src_off + nbytes > host_bytes (when the model has
+ * a host image), TG_PLAN_CONFIRM without a host image, model_id running in
  * the pool.  TG_ERR_NOSPACE: the tensors cannot be placed with the stages
  * that the flags allow.  `stream` is used only with TG_PLAN_CONFIRM.
  */
@@ -330,6 +397,13 @@ tg_status tg_plan_info(const tg_load_plan *plan, tg_plan_summary *out);
 tg_status tg_plan_moves(const tg_load_plan *plan, const tg_move **moves, uint32_t *n);
 tg_status tg_plan_evictions(const tg_load_plan *plan, const uint64_t **offsets, uint32_t *n);
 
+/* What the plan's device work took (see tg_timing); valid once tg_assemble or
+ * tg_assemble_wait has returned.  out [host]. */
+tg_status tg_plan_timing(const tg_load_plan *plan, tg_timing *out);
+
+/* Frees the plan.  If a load begun with it is still in flight (tg_assemble_async /
+ * _begin without _wait), the call first waits for the streams and gives the
+ * load up as a failed tg_assemble_wait would. */
 void tg_plan_free(tg_load_plan *plan);
 
 /*
@@ -393,6 +467,59 @@ tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_ar
                          void **out_dev_ptrs);
 
 /*
+ * The same load in steps that do not block.  (Section 3.1: tensors that are
+ * not found are loaded from the CPU-side Model Cache or the Model Store;
+ * Section 3.4, Eq. 3: Store-to-Cache and Cache-to-GPU transfers overlap.)
+ *
+ * tg_assemble_async  enqueues everything tg_assemble_ex does -- moves, the
+ *     gather, every host-to-device copy from the plan's host image, the
+ *     fingerprints of a verifying load -- and returns without waiting for the
+ *     device.  The plan must have a host image if it transfers anything.
+ * tg_assemble_begin  enqueues the part that needs no host bytes: moves, the
+ *     gather, and their fingerprints.  The missing tensors are then handed
+ *     over with tg_assemble_feed, in any order and any number of pieces, from
+ *     wherever in pinned memory they happen to be: a Model Cache smaller than
+ *     the model is refilled between feeds.  The plan's host image, if it has
+ *     one, is not touched.
+ * tg_assemble_feed   seg_base [pinned host] .. + seg_bytes holds the bytes of
+ *     the n tensors listed in rows [host]: tensor rows[i].tensor (an index
+ *     into the model's tensor list; it must be a TG_OP_H2D row of the plan
+ *     that has not been fed yet) starts at seg_base + rows[i].seg_off.  Their
+ *     copies are enqueued like tg_assemble's (merged where adjacent, dealt
+ *     over the two transfer streams, small ones through the gather kernel on
+ *     stream_gather, fingerprinted in batches as they land if the load
+ *     verifies) and the call returns.  *ticket [host], if not NULL, receives
+ *     a number for tg_assemble_feed_wait.  TG_ERR_INVALID for a row that is
+ *     out of range, not a transfer, fed twice, or that reaches past seg_bytes;
+ *     a feed refused for its rows enqueues nothing and the load goes on.
+ * tg_assemble_feed_wait  blocks until the device has read everything the
+ *     feed with that ticket reads from its segment, after which the caller
+ *     may overwrite the segment (with the next piece of the model).
+ * tg_assemble_wait   waits for the streams, checks the fingerprints of a
+ *     verifying load, commits and fills out_dev_ptrs exactly as tg_assemble
+ *     does, and ends the load.  TG_ERR_INVALID, after waiting, if a missing
+ *     tensor was never fed; then, and after any other failure, the load is
+ *     given up as described for tg_assemble.
+ * One load at a time may be in flight per pool; while it is, the pool accepts
+ * tg_plan, tg_reuse_size and the read-outs, and refuses commit, abandon,
+ * release and a second begin with TG_ERR_INVALID.  Any of these calls that
+ * fails after work was enqueued waits for the streams, gives the load up and
+ * ends it; the plan can then only be freed.  Loads on different pools are
+ * independent and may run from different threads at the same time.
+ */
+typedef struct {
+    uint32_t tensor;          /* index into the model's tensor list */
+    uint32_t reserved;        /* must be 0 */
+    uint64_t seg_off;         /* where the tensor's bytes start inside the segment */
+} tg_feed_row;
+tg_status tg_assemble_async(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args);
+tg_status tg_assemble_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args);
+tg_status tg_assemble_feed(tg_pool *pool, tg_load_plan *plan, const void *seg_base, uint64_t seg_bytes,
+                           const tg_feed_row *rows, uint32_t n, uint32_t *ticket);
+tg_status tg_assemble_feed_wait(tg_pool *pool, tg_load_plan *plan, uint32_t ticket);
+tg_status tg_assemble_wait(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs);
+
+/*
  * Commit a plan's metadata without enqueuing any copy, for a caller that
  * fills the slots itself (or only wants the bookkeeping).  Same checks and
  * same effect on the Region List and Tensor Mapping as tg_assemble.
@@ -443,31 +570,6 @@ tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double 
                         uint64_t *reuse_bytes, double *est_load_s);
 
 /*
- * Launch shape of the three streaming kernels.  *_unroll is the number of
- * independent 128-bit loads a lane issues per tile (2, 4, 8 or 16; a tile is
- * lanes x 16 B x unroll, with 256 lanes for fingerprint and compare and 1024
- * for the gather); *_wgs_per_cu is the number of workgroups launched per
- * compute unit.  h2d_kernel_max_bytes > 0 lets missing
- * tensors up to that size be fetched by the gather kernel through the pinned
- * buffer's device mapping instead of one copy-engine call each (default
- * 64 KiB: such a copy takes about 1 us on the link and about 10 us to issue).
- * The defaults are the measured optimum on MI355X; results never depend on
- * these values.
- */
-typedef struct {
-    uint32_t fingerprint_unroll, fingerprint_wgs_per_cu;
-    uint32_t gather_unroll, gather_wgs_per_cu;
-    uint32_t compare_unroll, compare_wgs_per_cu;
-    uint64_t h2d_kernel_max_bytes;
-} tg_tuning;
-tg_status tg_set_tuning(const tg_tuning *t);
-tg_status tg_get_tuning(tg_tuning *out);
-
-/* Profiling switch and read-out (see tg_timing). */
-void      tg_set_profiling(int on);
-tg_status tg_last_timing(tg_timing *out);
-
-/*
  * Page-locked host memory for a Model Cache image (Section 3.1 loads missing
  * tensors from the CPU-side Model Cache; the copy engine needs it pinned).
  * *out [pinned host] receives nbytes of memory that is also mapped into the
@@ -476,6 +578,13 @@ tg_status tg_last_timing(tg_timing *out);
  */
 tg_status tg_host_alloc(uint64_t nbytes, void **out);
 tg_status tg_host_free(void *p);
+
+/* The address under which kernels see a piece of pinned host memory (its
+ * device mapping): what to put into a tg_span or tg_pair that should read the
+ * Model Cache in place, over the host link.  pinned [pinned host] may point
+ * anywhere inside an allocation of tg_host_alloc (or any page-locked, mapped
+ * allocation).  TG_ERR_INVALID if the memory is not mapped for the device. */
+tg_status tg_host_device_ptr(const void *pinned, void **out_dev);
 
 /* Frees the library's device and pinned scratch.  Safe to call twice. */
 void tg_shutdown(void);

@@ -320,6 +320,27 @@ __global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copi
     }
 }
 
+// ------------------------------------------------------------------ mix rate
+// The fingerprint's arithmetic without its loads: every lane mixes
+// iters x 16 words that it makes up in registers (key and word advance by
+// constants, as in the tiles' inner loop).  Measures the integer-ALU limit of
+// the fingerprint; the sum is stored only if it hits one particular value, so
+// the work cannot be optimised away and nothing is written in practice.
+template <int T>
+__global__ __launch_bounds__(T) void mix_rate_kernel(u64 *__restrict__ sink, u32 iters, u64 seed) {
+    const u64 lane = u64(blockIdx.x) * T + threadIdx.x;
+    u64 key = lane * kGamma, w = seed ^ (lane << 17), acc = 0;
+    for (u32 it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            acc += mix(w ^ key);
+            key += kGamma;
+            w += 0x0123456789ABCDEFull;
+        }
+    }
+    if (acc == 0x5DEECE66D1CE4E5Bull) sink[0] = acc;
+}
+
 // Sets n 64-bit words to zero (result words of the kernels above).
 __global__ void zero_words_kernel(u64 *p, u32 n) {
     const u32 i = blockIdx.x * blockDim.x + threadIdx.x;

@@ -14,9 +14,6 @@
 #include "kernels.hip.h"
 #include "reuse_store.h"
 
-struct tg_pool { tg::ReuseStore store; tg_pool(uint64_t b, uint64_t c, uint32_t a) : store(b, c, a) {} };
-struct tg_load_plan { tg::Plan plan; std::vector<tg_plan_op> rows; std::vector<tg_move> move_rows; };
-
 namespace {
 
 using tgk::u32;
@@ -25,11 +22,9 @@ using tgk::u64;
 #define TG_HIP(call) do { if ((call) != hipSuccess) { (void)hipGetLastError(); return TG_ERR_HIP; } } while (0)
 
 // Loads in flight per lane (U) and resident workgroups per compute unit for
-// each kernel.  Chosen by measurement on MI355X; see tg_set_tuning.
-tg_tuning g_tune = {8, 4, 4, 1, 4, 2, uint64_t(64) << 10};
-
-bool g_profiling = false;
-tg_timing g_timing = {};
+// each kernel, the size up to which a missing tensor rides in the gather launch,
+// and the copy-grouping threshold (0: none).  Chosen by measurement on MI355X.
+constexpr tg_tuning kDefaultTuning = {8, 4, 4, 1, 4, 2, uint64_t(64) << 10, 0};
 
 // A move whose source and destination overlap goes through this much staging at a time.
 constexpr size_t kBounceBytes = size_t(128) << 20;
@@ -38,44 +33,37 @@ constexpr size_t kBounceBytes = size_t(128) << 20;
 // small to be worth their launch cost and the stretch is staged.
 constexpr uint64_t kDirectShift = uint64_t(32) << 20;
 
-// A verifying tg_assemble cuts the host-to-device copies into this many batches
-// and fingerprints each as soon as it has landed.
+// A verifying load cuts the host-to-device copies of a feed into this many
+// batches and fingerprints each as soon as it has landed.
 constexpr size_t kVerifyBatches = 4;
 // ... but only batches of at least this many bytes: a dependency between two
 // streams costs far more than a small copy (measured: a 9 MB model loads in
 // 0.16 ms when the host joins the streams and in 1.4 ms with four event waits).
 constexpr uint64_t kVerifyBatchMinBytes = uint64_t(64) << 20;
-// Events: 0-1 gather, 2-3 host-to-device stream, 4-5 moves, 6.. one pair per
-// verification group (gather, the batches, the moved tensors), then one per batch.
-constexpr int kBatchEvent0 = 6 + 2 * int(2 + kVerifyBatches);
-// ... and, for the second host-to-device stream, one more per batch and one for its end
-constexpr int kBatch2Event0 = kBatchEvent0 + int(kVerifyBatches);
-constexpr int kSecondDoneEvent = kBatch2Event0 + int(kVerifyBatches);
-constexpr int kEvents = kSecondDoneEvent + 1;
 
-// Library-owned scratch: one pinned staging buffer and one device buffer that
-// hold a launch's descriptor table, tile prefix and result words.
-struct Scratch {
-    std::mutex mu;
+// Library-owned device resources of one owner (a pool, or the calls that take
+// no pool): one pinned and one device buffer that hold descriptor tables, tile
+// prefixes and result words, the staging buffer of merge moves, and events.
+struct DeviceTables {
     void *h = nullptr, *d = nullptr;
     size_t cap = 0;
     int cu_count = 0;
-    int device = -1;                    // the one device this process's scratch lives on
-    hipEvent_t ev[kEvents] = {};
+    int device = -1;                    // the device these resources live on
+    std::vector<hipEvent_t> events;
     void *bounce = nullptr;             // staging for moves whose source and destination overlap
 
     tg_status init() {
         int dev = 0;
         TG_HIP(hipGetDevice(&dev));
         if (cu_count != 0) return dev == device ? TG_OK : TG_ERR_INVALID;
-        hipDeviceProp_t prop;
-        TG_HIP(hipGetDeviceProperties(&prop, dev));
-        for (auto &e : ev)
-            if (!e) TG_HIP(hipEventCreate(&e));
-        cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        int cus = 0;
+        TG_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        cu_count = cus > 0 ? cus : 256;
         device = dev;
         return TG_OK;
     }
+    // Room for `bytes` of tables.  Only called while nothing that reads the
+    // tables is in flight: growing replaces the buffers.
     tg_status ensure(size_t bytes) {
         const tg_status rc = init();
         if (rc != TG_OK) return rc;
@@ -98,14 +86,55 @@ struct Scratch {
         if (hipMalloc(&bounce, kBounceBytes) != hipSuccess) { bounce = nullptr; (void)hipGetLastError(); return TG_ERR_NOMEM; }
         return TG_OK;
     }
+    // Event number i of this owner, created on first use and kept.
+    tg_status event(size_t i, hipEvent_t *out) {
+        while (events.size() <= i) {
+            hipEvent_t e = nullptr;
+            TG_HIP(hipEventCreate(&e));
+            try { events.push_back(e); } catch (...) { (void)hipEventDestroy(e); return TG_ERR_NOMEM; }
+        }
+        *out = events[i];
+        return TG_OK;
+    }
     void shutdown() {
         release_buffers();
         if (bounce) { (void)hipFree(bounce); bounce = nullptr; }
-        for (auto &e : ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
+        for (auto &e : events) if (e) (void)hipEventDestroy(e);
+        events.clear();
         cu_count = 0;
         device = -1;
     }
-} g_scratch;
+};
+
+// Resources of tg_fingerprint / tg_compare, which take no pool.
+struct SharedTables {
+    std::mutex mu;
+    DeviceTables t;
+} g_shared;
+
+}  // namespace
+
+struct Session;
+
+struct tg_pool {
+    tg::ReuseStore store;
+    tg_tuning tune = kDefaultTuning;
+    bool profiling = false;
+    DeviceTables dev;
+    tg_load_plan *in_flight = nullptr;      // the plan whose load has begun and not ended
+    tg_pool(uint64_t b, uint64_t c, uint32_t a) : store(b, c, a) {}
+};
+
+struct tg_load_plan {
+    tg::Plan plan;
+    std::vector<tg_plan_op> rows;
+    std::vector<tg_move> move_rows;
+    tg_timing timing = {};
+    tg_pool *pool = nullptr;
+    Session *session = nullptr;             // between begin and the end of the load
+};
+
+namespace {
 
 size_t align_up(size_t n, size_t a) { return (n + a - 1) / a * a; }
 
@@ -135,8 +164,8 @@ bool fill_prefix(u32 *prefix, const u64 *nbytes, size_t stride_words, size_t n, 
     return true;
 }
 
-u32 grid_for(u32 total_tiles, u32 wgs_per_cu) {
-    const u64 resident = u64(g_scratch.cu_count) * std::max<u32>(1, wgs_per_cu);
+u32 grid_for(int cu_count, u32 total_tiles, u32 wgs_per_cu) {
+    const u64 resident = u64(cu_count) * std::max<u32>(1, wgs_per_cu);
     return u32(std::max<u64>(1, std::min<u64>(total_tiles, resident)));
 }
 
@@ -163,6 +192,113 @@ struct DrainOnExit {
     explicit DrainOnExit(hipStream_t s) : st(s) {}
     ~DrainOnExit() { if (armed) { (void)hipStreamSynchronize(st); (void)hipGetLastError(); } }
 };
+
+// One fingerprint launch over a span table that is already on the device.
+tg_status launch_fingerprint(const DeviceTables &T, const tg_tuning &tune, size_t desc_off, size_t prefix_off,
+                             size_t result_off, u32 n, u32 tiles, hipStream_t st) {
+    if (tiles == 0) return TG_OK;
+    const u32 U = pick_u(tune.fingerprint_unroll);
+    char *d = static_cast<char *>(T.d);
+    const u32 grid = grid_for(T.cu_count, tiles, tune.fingerprint_wgs_per_cu);
+    const u32 run = run_for(tiles, grid);
+    TG_FOR_U(U, tgk::fingerprint_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, st>>>(
+                    reinterpret_cast<const tgk::Span *>(d + desc_off), reinterpret_cast<const u32 *>(d + prefix_off),
+                    n, run, reinterpret_cast<u64 *>(d + result_off)));
+    TG_HIP(hipGetLastError());
+    return TG_OK;
+}
+
+// ---- fingerprint over device-visible spans, with tables T (the caller holds
+// whatever lock protects them)
+tg_status fingerprint_run(DeviceTables &T, const tg_tuning &tune, const tg_span *spans, u32 n, uint64_t *out_fp,
+                          hipStream_t st, float *ms_out) {
+    const u32 U = pick_u(tune.fingerprint_unroll);
+    const TableLayout L = table_layout(n, sizeof(tgk::Span), sizeof(u64));
+    tg_status rc = T.ensure(L.total);
+    if (rc != TG_OK) return rc;
+    char *h = static_cast<char *>(T.h), *d = static_cast<char *>(T.d);
+    tgk::Span *hs = reinterpret_cast<tgk::Span *>(h + L.desc_off);
+    for (u32 i = 0; i < n; ++i) {
+        hs[i].ptr = u64(reinterpret_cast<uintptr_t>(spans[i].ptr));
+        hs[i].nbytes = spans[i].nbytes;
+    }
+    u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
+    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, n, tile_for(tgk::kReadThreads, U))) return TG_ERR_INVALID;
+    const u32 total_tiles = hp[n];
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (ms_out) {
+        if ((rc = T.event(0, &e0)) != TG_OK || (rc = T.event(1, &e1)) != TG_OK) return rc;
+    }
+    u64 *d_out = reinterpret_cast<u64 *>(d + L.result_off);
+    u64 *h_out = reinterpret_cast<u64 *>(h + L.result_off);
+    DrainOnExit drain(st);
+    TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_out, n);
+    if (ms_out && total_tiles > 0) TG_HIP(hipEventRecord(e0, st));
+    rc = launch_fingerprint(T, tune, L.desc_off, L.prefix_off, L.result_off, n, total_tiles, st);
+    if (rc != TG_OK) return rc;
+    if (ms_out && total_tiles > 0) TG_HIP(hipEventRecord(e1, st));
+    TG_HIP(hipMemcpyAsync(h_out, d_out, n * sizeof(u64), hipMemcpyDeviceToHost, st));
+    TG_HIP(hipStreamSynchronize(st));
+    drain.armed = false;
+    if (ms_out) {
+        float ms = 0.f;
+        if (total_tiles > 0) TG_HIP(hipEventElapsedTime(&ms, e0, e1));
+        *ms_out = ms;
+    }
+    std::memcpy(out_fp, h_out, n * sizeof(u64));
+    return TG_OK;
+}
+
+tg_status compare_run(DeviceTables &T, const tg_tuning &tune, const tg_pair *pairs, u32 n, uint32_t *out_differs,
+                      hipStream_t st, float *ms_out) {
+    const u32 U = pick_u(tune.compare_unroll);
+    const TableLayout L = table_layout(n, sizeof(tgk::Pair), sizeof(u64));
+    tg_status rc = T.ensure(L.total);
+    if (rc != TG_OK) return rc;
+    char *h = static_cast<char *>(T.h), *d = static_cast<char *>(T.d);
+    tgk::Pair *hs = reinterpret_cast<tgk::Pair *>(h + L.desc_off);
+    for (u32 i = 0; i < n; ++i) {
+        hs[i].a = u64(reinterpret_cast<uintptr_t>(pairs[i].a));
+        hs[i].b = u64(reinterpret_cast<uintptr_t>(pairs[i].b));
+        hs[i].nbytes = pairs[i].nbytes;
+    }
+    u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
+    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Pair) / 8, n, tile_for(tgk::kReadThreads, U))) return TG_ERR_INVALID;
+    const u32 total_tiles = hp[n];
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (ms_out) {
+        if ((rc = T.event(0, &e0)) != TG_OK || (rc = T.event(1, &e1)) != TG_OK) return rc;
+    }
+    // results are 32-bit flags; the zero kernel clears whole 64-bit words
+    u32 *d_out = reinterpret_cast<u32 *>(d + L.result_off);
+    u32 *h_out = reinterpret_cast<u32 *>(h + L.result_off);
+    DrainOnExit drain(st);
+    TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
+    const u32 words = (n + 1) / 2;
+    hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((words + 255) / 256), dim3(256), 0, st,
+                       reinterpret_cast<u64 *>(d_out), words);
+    if (total_tiles > 0) {
+        const u32 grid = grid_for(T.cu_count, total_tiles, tune.compare_wgs_per_cu);
+        if (ms_out) TG_HIP(hipEventRecord(e0, st));
+        const u32 run = run_for(total_tiles, grid);
+        TG_FOR_U(U, tgk::compare_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, st>>>(
+                        reinterpret_cast<const tgk::Pair *>(d + L.desc_off),
+                        reinterpret_cast<const u32 *>(d + L.prefix_off), n, run, d_out));
+        TG_HIP(hipGetLastError());
+        if (ms_out) TG_HIP(hipEventRecord(e1, st));
+    }
+    TG_HIP(hipMemcpyAsync(h_out, d_out, n * sizeof(u32), hipMemcpyDeviceToHost, st));
+    TG_HIP(hipStreamSynchronize(st));
+    drain.armed = false;
+    if (ms_out) {
+        float ms = 0.f;
+        if (total_tiles > 0) TG_HIP(hipEventElapsedTime(&ms, e0, e1));
+        *ms_out = ms;
+    }
+    std::memcpy(out_differs, h_out, n * sizeof(u32));
+    return TG_OK;
+}
 
 // ---- scratch of the entry point that allocates nothing (tg_fingerprint_noalloc)
 //
@@ -200,100 +336,6 @@ tg_status static_scratch_for(int device, unsigned char **ptr, int *cus) {
     return TG_OK;
 }
 
-// ---- fingerprint over device-visible spans; scratch lock held by the caller
-tg_status fingerprint_locked(const tg_span *spans, u32 n, uint64_t *out_fp, hipStream_t st,
-                             float *ms_out, uint64_t *bytes_out) {
-    const u32 U = pick_u(g_tune.fingerprint_unroll);
-    const TableLayout L = table_layout(n, sizeof(tgk::Span), sizeof(u64));
-    tg_status rc = g_scratch.ensure(L.total);
-    if (rc != TG_OK) return rc;
-    char *h = static_cast<char *>(g_scratch.h), *d = static_cast<char *>(g_scratch.d);
-    tgk::Span *hs = reinterpret_cast<tgk::Span *>(h + L.desc_off);
-    u64 total_bytes = 0;
-    for (u32 i = 0; i < n; ++i) {
-        hs[i].ptr = u64(reinterpret_cast<uintptr_t>(spans[i].ptr));
-        hs[i].nbytes = spans[i].nbytes;
-        total_bytes += spans[i].nbytes;
-    }
-    u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
-    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, n, tile_for(tgk::kReadThreads, U))) return TG_ERR_INVALID;
-    const u32 total_tiles = hp[n];
-    u64 *d_out = reinterpret_cast<u64 *>(d + L.result_off);
-    u64 *h_out = reinterpret_cast<u64 *>(h + L.result_off);
-    DrainOnExit drain(st);
-    TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
-    hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_out, n);
-    if (total_tiles > 0) {
-        const u32 grid = grid_for(total_tiles, g_tune.fingerprint_wgs_per_cu);
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], st));
-        const u32 run = run_for(total_tiles, grid);
-        TG_FOR_U(U, tgk::fingerprint_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, st>>>(
-                        reinterpret_cast<const tgk::Span *>(d + L.desc_off),
-                        reinterpret_cast<const u32 *>(d + L.prefix_off), n, run, d_out));
-        TG_HIP(hipGetLastError());
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], st));
-    }
-    TG_HIP(hipMemcpyAsync(h_out, d_out, n * sizeof(u64), hipMemcpyDeviceToHost, st));
-    TG_HIP(hipStreamSynchronize(st));
-    drain.armed = false;
-    if (g_profiling && ms_out) {
-        float ms = 0.f;
-        if (total_tiles > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
-        *ms_out = ms;
-        if (bytes_out) *bytes_out = total_bytes;
-    }
-    std::memcpy(out_fp, h_out, n * sizeof(u64));
-    return TG_OK;
-}
-
-tg_status compare_locked(const tg_pair *pairs, u32 n, uint32_t *out_differs, hipStream_t st) {
-    const u32 U = pick_u(g_tune.compare_unroll);
-    const TableLayout L = table_layout(n, sizeof(tgk::Pair), sizeof(u64));
-    tg_status rc = g_scratch.ensure(L.total);
-    if (rc != TG_OK) return rc;
-    char *h = static_cast<char *>(g_scratch.h), *d = static_cast<char *>(g_scratch.d);
-    tgk::Pair *hs = reinterpret_cast<tgk::Pair *>(h + L.desc_off);
-    u64 total_bytes = 0;
-    for (u32 i = 0; i < n; ++i) {
-        hs[i].a = u64(reinterpret_cast<uintptr_t>(pairs[i].a));
-        hs[i].b = u64(reinterpret_cast<uintptr_t>(pairs[i].b));
-        hs[i].nbytes = pairs[i].nbytes;
-        total_bytes += pairs[i].nbytes;
-    }
-    u32 *hp = reinterpret_cast<u32 *>(h + L.prefix_off);
-    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Pair) / 8, n, tile_for(tgk::kReadThreads, U))) return TG_ERR_INVALID;
-    const u32 total_tiles = hp[n];
-    // results are 32-bit flags; the zero kernel clears whole 64-bit words
-    u32 *d_out = reinterpret_cast<u32 *>(d + L.result_off);
-    u32 *h_out = reinterpret_cast<u32 *>(h + L.result_off);
-    DrainOnExit drain(st);
-    TG_HIP(hipMemcpyAsync(d, h, L.result_off, hipMemcpyHostToDevice, st));
-    const u32 words = (n + 1) / 2;
-    hipLaunchKernelGGL(tgk::zero_words_kernel, dim3((words + 255) / 256), dim3(256), 0, st,
-                       reinterpret_cast<u64 *>(d_out), words);
-    if (total_tiles > 0) {
-        const u32 grid = grid_for(total_tiles, g_tune.compare_wgs_per_cu);
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], st));
-        const u32 run = run_for(total_tiles, grid);
-        TG_FOR_U(U, tgk::compare_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, st>>>(
-                        reinterpret_cast<const tgk::Pair *>(d + L.desc_off),
-                        reinterpret_cast<const u32 *>(d + L.prefix_off), n, run, d_out));
-        TG_HIP(hipGetLastError());
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], st));
-    }
-    TG_HIP(hipMemcpyAsync(h_out, d_out, n * sizeof(u32), hipMemcpyDeviceToHost, st));
-    TG_HIP(hipStreamSynchronize(st));
-    drain.armed = false;
-    if (g_profiling) {
-        float ms = 0.f;
-        if (total_tiles > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
-        g_timing.compare_ms = ms;
-        g_timing.compare_bytes = total_bytes;
-    }
-    std::memcpy(out_differs, h_out, n * sizeof(u32));
-    return TG_OK;
-}
-
 // Merge moves as copy launches (Section 3.2, Stage 2).  Moves arrive in
 // execution order: ascending addresses, each shifting its tensor towards lower
 // addresses inside its own subspace.  Seen as one stream of bytes, a byte's
@@ -304,10 +346,9 @@ tg_status compare_locked(const tg_pair *pairs, u32 n, uint32_t *out_differs, hip
 // reads: a stretch whose first byte shifts by d can be copied straight, up to d
 // bytes per launch.  When d is small the stretch is staged instead: one launch
 // gathers up to kBounceBytes into the staging buffer, the next writes them out.
-tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
+tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base, u64 bounce,
                               std::vector<std::vector<tgk::Copy>> &launches, u64 &traffic) {
     traffic = 0;
-    const u64 bounce = u64(reinterpret_cast<uintptr_t>(g_scratch.bounce));
     size_t i = 0;
     uint64_t done = 0;                      // bytes of moves[i] already scheduled
     while (i < moves.size()) {
@@ -361,8 +402,8 @@ tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
 // touch a source of the same launch, and every extent lies in the pool or in
 // the staging buffer.  A mistake in the cutting above then comes back as an
 // error code instead of moved tensors that overwrote each other.
-tg_status check_move_launches(const std::vector<std::vector<tgk::Copy>> &launches, uint64_t base, uint64_t cap) {
-    const u64 bounce = u64(reinterpret_cast<uintptr_t>(g_scratch.bounce));
+tg_status check_move_launches(const std::vector<std::vector<tgk::Copy>> &launches, uint64_t base, uint64_t cap,
+                              u64 bounce) {
     auto inside = [&](u64 a, u64 n) {
         const bool in_pool = a >= base && n <= cap && a - base <= cap - n;
         const bool in_bounce = bounce != 0 && a >= bounce && n <= kBounceBytes && a - bounce <= kBounceBytes - n;
@@ -410,7 +451,7 @@ tg_status validate_plan(const tg::Plan &pl, const tg::ReuseStore &store) {
                 if (op.dst_off != op.src_off) return TG_ERR_INVALID;
                 continue;                                   // nothing is written
             }
-        } else if (op.src_off > pl.host_bytes || op.nbytes > pl.host_bytes - op.src_off) {
+        } else if (pl.host_base && (op.src_off > pl.host_bytes || op.nbytes > pl.host_bytes - op.src_off)) {
             return TG_ERR_INVALID;
         }
         dst.push_back({op.dst_off, op.dst_off + op.nbytes});
@@ -448,13 +489,599 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 tg_status check_model(const tg_model_desc *m, std::vector<tg::TensorIn> &tensors) {
     if (!m || !m->tensors || m->n_tensors == 0 || m->reserved != 0) return TG_ERR_INVALID;
+    if (!m->host_base && m->host_bytes != 0) return TG_ERR_INVALID;
     tensors.resize(m->n_tensors);
     for (u32 k = 0; k < m->n_tensors; ++k) {
         const tg_tensor_desc &t = m->tensors[k];
         if (t.nbytes == 0) return TG_ERR_INVALID;
-        if (t.src_off > m->host_bytes || t.nbytes > m->host_bytes - t.src_off) return TG_ERR_INVALID;
+        // without a host image src_off is the caller's own reference and is not checked
+        if (m->host_base && (t.src_off > m->host_bytes || t.nbytes > m->host_bytes - t.src_off)) return TG_ERR_INVALID;
         tensors[k] = tg::TensorIn{t.nbytes, t.fp, t.src_off};
     }
+    return TG_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ load session
+// The state of one load between its first enqueued work and its commit:
+// which tensors have been handed over, where the next table goes inside the
+// pool's scratch, which events time or order what.  tg_assemble runs one from
+// start to end inside a single call; tg_assemble_begin / _feed / _wait spread
+// it over several.
+struct Session {
+    tg_pool *pool = nullptr;
+    tg_load_plan *lp = nullptr;
+    hipStream_t sg = nullptr, sh = nullptr, sh2 = nullptr;
+    bool dual = false, verify = false, prof = false;
+    // tables are placed one after the other inside the pool's scratch; [0, uploaded)
+    // of the pinned copy has been sent to the device copy
+    size_t used = 0, uploaded = 0, cap = 0;
+    size_t results_off = 0;
+    u32 results_cap = 0, results_used = 0;
+    std::vector<int64_t> result_ref;        // result word -> tensor index, or -1 - (index of a move)
+    std::vector<char> fed;                  // per tensor: nothing (more) to hand over
+    u32 unfed = 0;
+    size_t next_event = 0;
+    struct EvPair { hipEvent_t a, b; };
+    std::vector<EvPair> verify_ev, h2d_ev;
+    EvPair gather_ev{}, move_ev{};
+    bool timed_gather = false, timed_moves = false;
+    struct Ticket { hipEvent_t transfer, kernel; };   // null: that stream read nothing of the segment
+    std::vector<Ticket> tickets;
+    u32 copy_no = 0;                        // host-to-device copies issued so far (deals them over two streams)
+    tg_timing t = {};
+    std::vector<uint64_t> corrupt_moved;    // moved tensors that no longer match their rows
+    bool wrote = false;                     // work that writes into the pool has been enqueued
+};
+
+namespace {
+
+struct FeedItem { u32 k; const char *src; };            // tensor index, host address of its bytes
+struct FpLaunch { size_t desc_off = 0, prefix_off = 0, result_off = 0; u32 n = 0, tiles = 0; u64 bytes = 0; };
+struct CopyLaunch { size_t desc_off = 0, prefix_off = 0, ticket_off = 0; u32 n = 0, tiles = 0; };
+
+char *tab_h(Session &s) { return static_cast<char *>(s.pool->dev.h); }
+char *tab_d(Session &s) { return static_cast<char *>(s.pool->dev.d); }
+
+tg_status tab_alloc(Session &s, size_t bytes, size_t *off) {
+    const size_t at = align_up(s.used, 256);
+    if (at + bytes > s.cap) return TG_ERR_NOMEM;        // the bound computed at begin was wrong
+    s.used = at + bytes;
+    *off = at;
+    return TG_OK;
+}
+
+tg_status new_event(Session &s, hipEvent_t *e) { return s.pool->dev.event(s.next_event++, e); }
+
+// Sends what has been written into the pinned tables since the last upload.
+tg_status upload_tables(Session &s) {
+    if (s.used > s.uploaded)
+        TG_HIP(hipMemcpyAsync(tab_d(s) + s.uploaded, tab_h(s) + s.uploaded, s.used - s.uploaded,
+                              hipMemcpyHostToDevice, s.sg));
+    s.uploaded = s.used;
+    return TG_OK;
+}
+
+// Table of one copy launch (rows, tile prefix, ticket counter) in the pinned scratch.
+tg_status place_copy_launch(Session &s, const std::vector<tgk::Copy> &rows, CopyLaunch &out) {
+    const u64 tile = tile_for(tgk::kCopyThreads, pick_u(s.pool->tune.gather_unroll));
+    tg_status rc;
+    if ((rc = tab_alloc(s, rows.size() * sizeof(tgk::Copy), &out.desc_off)) != TG_OK) return rc;
+    if ((rc = tab_alloc(s, (rows.size() + 1) * sizeof(u32), &out.prefix_off)) != TG_OK) return rc;
+    if ((rc = tab_alloc(s, 256, &out.ticket_off)) != TG_OK) return rc;
+    char *h = tab_h(s);
+    std::memcpy(h + out.desc_off, rows.data(), rows.size() * sizeof(tgk::Copy));
+    u32 *hp = reinterpret_cast<u32 *>(h + out.prefix_off);
+    if (!fill_prefix(hp, &rows[0].nbytes, sizeof(tgk::Copy) / 8, rows.size(), tile)) return TG_ERR_INVALID;
+    out.n = u32(rows.size());
+    out.tiles = hp[rows.size()];
+    std::memset(h + out.ticket_off, 0, 256);            // the launch's tile counter starts at zero
+    return TG_OK;
+}
+
+tg_status launch_copy(Session &s, const CopyLaunch &c) {
+    if (c.tiles == 0) return TG_OK;
+    const tg_tuning &tune = s.pool->tune;
+    const u32 U = pick_u(tune.gather_unroll);
+    char *d = tab_d(s);
+    const u32 grid = grid_for(s.pool->dev.cu_count, c.tiles, tune.gather_wgs_per_cu);
+    TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU><<<dim3(grid), dim3(tgk::kCopyThreads), 0, s.sg>>>(
+                    reinterpret_cast<const tgk::Copy *>(d + c.desc_off),
+                    reinterpret_cast<const u32 *>(d + c.prefix_off), c.n, reinterpret_cast<u32 *>(d + c.ticket_off)));
+    TG_HIP(hipGetLastError());
+    return TG_OK;
+}
+
+// Span table of one verification launch: the slots of tensors `ops`, or (moved)
+// every tensor the plan moves, at its new address.  Result words are handed out
+// in order; result_ref remembers whose each is.
+tg_status place_verify(Session &s, const std::vector<u32> &ops, bool moved, FpLaunch &out) {
+    const tg::Plan &pl = s.lp->plan;
+    const size_t rows = moved ? pl.moves.size() : ops.size();
+    out = FpLaunch{};
+    if (rows == 0) return TG_OK;
+    if (s.results_used + rows > s.results_cap) return TG_ERR_NOMEM;
+    tg_status rc;
+    if ((rc = tab_alloc(s, rows * sizeof(tgk::Span), &out.desc_off)) != TG_OK) return rc;
+    if ((rc = tab_alloc(s, (rows + 1) * sizeof(u32), &out.prefix_off)) != TG_OK) return rc;
+    const uint64_t base = s.pool->store.base();
+    char *h = tab_h(s);
+    tgk::Span *hs = reinterpret_cast<tgk::Span *>(h + out.desc_off);
+    for (size_t i = 0; i < rows; ++i) {
+        hs[i].ptr = base + (moved ? pl.moves[i].new_off : pl.ops[ops[i]].dst_off);
+        hs[i].nbytes = moved ? pl.moves[i].nbytes : pl.ops[ops[i]].nbytes;
+        out.bytes += hs[i].nbytes;
+        s.result_ref.push_back(moved ? -1 - int64_t(i) : int64_t(ops[i]));
+    }
+    u32 *hp = reinterpret_cast<u32 *>(h + out.prefix_off);
+    const u64 fp_tile = tile_for(tgk::kReadThreads, pick_u(s.pool->tune.fingerprint_unroll));
+    if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, rows, fp_tile)) return TG_ERR_INVALID;
+    out.n = u32(rows);
+    out.tiles = hp[rows];
+    out.result_off = s.results_off + size_t(s.results_used) * sizeof(u64);
+    s.results_used += u32(rows);
+    return TG_OK;
+}
+
+tg_status launch_verify(Session &s, const FpLaunch &f) {
+    if (f.tiles == 0) return TG_OK;
+    Session::EvPair ev{};
+    tg_status rc;
+    if (s.prof) {
+        if ((rc = new_event(s, &ev.a)) != TG_OK || (rc = new_event(s, &ev.b)) != TG_OK) return rc;
+        TG_HIP(hipEventRecord(ev.a, s.sg));
+    }
+    rc = launch_fingerprint(s.pool->dev, s.pool->tune, f.desc_off, f.prefix_off, f.result_off, f.n, f.tiles, s.sg);
+    if (rc != TG_OK) return rc;
+    if (s.prof) {
+        TG_HIP(hipEventRecord(ev.b, s.sg));
+        s.verify_ev.push_back(ev);
+    }
+    s.t.verify_bytes += f.bytes;
+    s.t.verify_launches += 1;
+    return TG_OK;
+}
+
+// Ends a load that cannot go on: nothing of it may still be running when the
+// tables are reused, and the Tensor Mapping must describe the pool's bytes.
+tg_status session_fail(tg_load_plan *lp, tg_status rc) {
+    Session *s = lp->session;
+    if (!s) return rc;
+    (void)hipStreamSynchronize(s->sg);
+    if (s->sh != s->sg) (void)hipStreamSynchronize(s->sh);
+    if (s->dual) (void)hipStreamSynchronize(s->sh2);
+    (void)hipGetLastError();
+    tg::ReuseStore &store = s->pool->store;
+    tg::Plan &pl = lp->plan;
+    // evicted tensors may have been overwritten and moved ones have moved:
+    // record that much (a plan that did neither has only written into free regions)
+    if (s->wrote && (!pl.moves.empty() || !pl.evict.empty())) (void)store.abandon(pl);
+    store.drop_corrupt(s->corrupt_moved);
+    lp->timing = s->t;
+    s->pool->in_flight = nullptr;
+    lp->session = nullptr;
+    delete s;
+    return rc;
+}
+
+// Host-to-device part of a feed: `items` are missing tensors whose bytes lie at
+// items[i].src (pinned).  Those in `small` have already been dealt with by a
+// gather launch.  Copies adjacent on both sides (the slot padding included)
+// are merged (Section 4 groups adjacent tensors into large copies); a
+// verifying load cuts them into batches and fingerprints each on stream A as
+// soon as it has landed on stream B.
+tg_status feed_transfers(Session &s, const std::vector<FeedItem> &items, bool may_block, hipEvent_t *done) {
+    *done = nullptr;
+    if (items.empty()) return TG_OK;
+    tg::ReuseStore &store = s.pool->store;
+    const tg::Plan &pl = s.lp->plan;
+    const uint64_t base = store.base();
+    const uint64_t group_limit = s.pool->tune.h2d_group_bytes;
+    struct H2D { uint64_t dst; const char *src; uint64_t len, padded; std::vector<u32> ops; };
+    std::vector<H2D> h2d;
+    h2d.reserve(items.size());
+    for (const FeedItem &it : items) {
+        const tg::Op &op = pl.ops[it.k];
+        h2d.push_back(H2D{op.dst_off, it.src, op.nbytes, store.round_up(op.nbytes), {it.k}});
+    }
+    std::sort(h2d.begin(), h2d.end(), [](const H2D &a, const H2D &b) { return a.dst < b.dst; });
+    std::vector<H2D> merged;
+    u64 total = 0;
+    for (H2D &c : h2d) {
+        total += c.len;
+        if (!merged.empty()) {
+            H2D &m = merged.back();
+            if (m.dst + m.padded == c.dst && m.src + m.padded == c.src && (group_limit == 0 || m.len <= group_limit)) {
+                m.len = m.padded + c.len;
+                m.padded += c.padded;
+                m.ops.push_back(c.ops[0]);
+                continue;
+            }
+        }
+        merged.push_back(std::move(c));
+    }
+    // batch_end[j] = index one past the last merged copy of batch j
+    std::vector<size_t> batch_end;
+    const size_t nb = !s.verify ? 1 : std::max<size_t>(1, std::min<size_t>(
+        std::min<size_t>(kVerifyBatches, merged.size()), size_t(total / kVerifyBatchMinBytes)));
+    {
+        // shares nb : nb-1 : ... : 1, so that little is left to fingerprint when the last copy lands
+        const u64 denom = u64(nb) * (nb + 1) / 2;
+        u64 acc = 0, cum = nb;
+        for (size_t i = 0; i < merged.size(); ++i) {
+            acc += merged[i].len;
+            const size_t have = batch_end.size();
+            if (i + 1 == merged.size() || (have + 1 < nb && acc * denom >= total * cum)) {
+                batch_end.push_back(i + 1);
+                cum += nb - (have + 1);
+            }
+        }
+    }
+    std::vector<FpLaunch> fp(batch_end.size());
+    tg_status rc;
+    if (s.verify) {
+        size_t from = 0;
+        std::vector<u32> ops;
+        for (size_t j = 0; j < batch_end.size(); ++j) {
+            ops.clear();
+            for (size_t i = from; i < batch_end[j]; ++i) ops.insert(ops.end(), merged[i].ops.begin(), merged[i].ops.end());
+            if ((rc = place_verify(s, ops, false, fp[j])) != TG_OK) return rc;
+            from = batch_end[j];
+        }
+        if ((rc = upload_tables(s)) != TG_OK) return rc;
+    }
+    Session::EvPair timed{};
+    if (s.prof) {
+        if ((rc = new_event(s, &timed.a)) != TG_OK || (rc = new_event(s, &timed.b)) != TG_OK) return rc;
+        TG_HIP(hipEventRecord(timed.a, s.sh));
+    }
+    s.wrote = true;
+    size_t from = 0;
+    bool any2 = false;
+    for (size_t j = 0; j < batch_end.size(); ++j) {
+        bool used2 = false;
+        for (size_t i = from; i < batch_end[j]; ++i) {
+            const H2D &c = merged[i];
+            const bool second = s.dual && (s.copy_no & 1) != 0;
+            TG_HIP(hipMemcpyAsync(reinterpret_cast<void *>(uintptr_t(base + c.dst)), c.src, c.len,
+                                  hipMemcpyHostToDevice, second ? s.sh2 : s.sh));
+            used2 = used2 || second;
+            s.copy_no += 1;
+            s.t.h2d_bytes += c.len;
+            s.t.h2d_copies += 1;
+        }
+        any2 = any2 || used2;
+        from = batch_end[j];
+        if (s.verify) {
+            if (s.sh != s.sg && may_block && total < kVerifyBatchMinBytes) {
+                TG_HIP(hipStreamSynchronize(s.sh));        // small transfer: the host joins
+                if (used2) TG_HIP(hipStreamSynchronize(s.sh2));
+            } else if (s.sh != s.sg) {
+                hipEvent_t e;
+                if ((rc = new_event(s, &e)) != TG_OK) return rc;
+                TG_HIP(hipEventRecord(e, s.sh));
+                TG_HIP(hipStreamWaitEvent(s.sg, e, 0));
+                if (used2) {
+                    if ((rc = new_event(s, &e)) != TG_OK) return rc;
+                    TG_HIP(hipEventRecord(e, s.sh2));
+                    TG_HIP(hipStreamWaitEvent(s.sg, e, 0));
+                }
+            }
+            if ((rc = launch_verify(s, fp[j])) != TG_OK) return rc;
+        }
+    }
+    if (any2) {                                   // stream B's end covers the second stream
+        hipEvent_t e;
+        if ((rc = new_event(s, &e)) != TG_OK) return rc;
+        TG_HIP(hipEventRecord(e, s.sh2));
+        TG_HIP(hipStreamWaitEvent(s.sh, e, 0));
+    }
+    if (s.prof) {
+        TG_HIP(hipEventRecord(timed.b, s.sh));
+        s.h2d_ev.push_back(timed);
+        *done = timed.b;
+    } else {
+        hipEvent_t e;
+        if ((rc = new_event(s, &e)) != TG_OK) return rc;
+        TG_HIP(hipEventRecord(e, s.sh));
+        *done = e;
+    }
+    return TG_OK;
+}
+
+// Splits the tensors of a feed into those that ride in a gather launch (read
+// through the pinned memory's device mapping) and those the copy engine takes.
+void split_small(const Session &s, const std::vector<FeedItem> &items, const void *host_base, void *host_dev,
+                 std::vector<tgk::Copy> &small_rows, std::vector<u32> &small_ops, std::vector<FeedItem> &dma) {
+    const tg::Plan &pl = s.lp->plan;
+    const uint64_t base = s.pool->store.base();
+    const uint64_t small = s.pool->tune.h2d_kernel_max_bytes;
+    for (const FeedItem &it : items) {
+        const tg::Op &op = pl.ops[it.k];
+        const u64 mapped = u64(uintptr_t(host_dev)) + u64(it.src - static_cast<const char *>(host_base));
+        if (host_dev && small > 0 && op.nbytes <= small && (mapped & 15u) == 0) {
+            small_rows.push_back(tgk::Copy{base + op.dst_off, mapped, op.nbytes});
+            small_ops.push_back(it.k);
+        } else {
+            dma.push_back(it);
+        }
+    }
+}
+
+size_t first_dma_count(const std::vector<FeedItem> *v) { return v ? v->size() : 0; }
+
+void *device_mapping(const void *pinned) {
+    void *dev = nullptr;
+    if (!pinned || hipHostGetDevicePointer(&dev, const_cast<void *>(pinned), 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return dev;
+}
+
+// Starts a load: checks, tables, moves, gather, the fingerprints that need no
+// host bytes.  With `image` (the plan's host image) the load is the classic one:
+// its small missing tensors ride in the gather launch and `first_dma` receives
+// the rest of the missing tensors for the caller to pass to feed_transfers.
+tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args, bool image,
+                        std::vector<FeedItem> *first_dma) {
+    if (!pool || !plan || !args) return TG_ERR_INVALID;
+    if (args->flags & ~TG_ASSEMBLE_VERIFY) return TG_ERR_INVALID;
+    tg::ReuseStore &store = pool->store;
+    tg::Plan &pl = plan->plan;
+    if (pl.consumed || pl.pool_tag != &store || plan->session || pool->in_flight) return TG_ERR_INVALID;
+    if (pl.generation != store.generation()) return TG_ERR_STALE;
+    if (store.model_active(pl.model_id)) return TG_ERR_INVALID;
+    if (image && pl.transfer_bytes > 0 && !pl.host_base) return TG_ERR_INVALID;
+    tg_status rc = validate_plan(pl, store);
+    if (rc != TG_OK) return rc;
+    if ((rc = pool->dev.init()) != TG_OK) return rc;
+    const uint64_t base = store.base();
+    const bool verify = (args->flags & TG_ASSEMBLE_VERIFY) != 0;
+
+    // ---- merge moves (Section 3.2, Stage 2), cut into launches whose reads and writes do not meet
+    std::vector<std::vector<tgk::Copy>> move_rows;
+    u64 move_traffic = 0;
+    if (!pl.moves.empty()) {
+        if ((rc = pool->dev.ensure_bounce()) != TG_OK) return rc;
+        const u64 bounce = u64(reinterpret_cast<uintptr_t>(pool->dev.bounce));
+        if ((rc = build_move_launches(pl.moves, base, bounce, move_rows, move_traffic)) != TG_OK) return rc;
+        if ((rc = check_move_launches(move_rows, base, store.capacity(), bounce)) != TG_OK) return rc;
+    }
+
+    Session *sp = new (std::nothrow) Session();
+    if (!sp) return TG_ERR_NOMEM;
+    struct Guard { Session *s; ~Guard() { delete s; } } guard{sp};
+    Session &s = *sp;
+    s.pool = pool;
+    s.lp = plan;
+    s.sg = static_cast<hipStream_t>(args->stream_gather);
+    s.sh = static_cast<hipStream_t>(args->stream_h2d);
+    // The copies may be dealt over two streams: one copy then starts while the other is still
+    // running, which hides what a copy costs to start (about 10 us each on one stream).
+    s.sh2 = args->use_second_h2d_stream ? static_cast<hipStream_t>(args->stream_h2d_second) : s.sh;
+    s.dual = s.sh2 != s.sh && s.sh2 != s.sg && s.sh != s.sg;
+    if (!s.dual) s.sh2 = s.sh;
+    s.verify = verify;
+    s.prof = pool->profiling;
+    s.t = plan->timing;                                   // keeps what tg_plan measured
+    s.t.gather_ms = s.t.h2d_ms = s.t.verify_ms = s.t.move_ms = 0.f;
+    s.t.gather_bytes = s.t.h2d_bytes = s.t.verify_bytes = s.t.move_bytes = s.t.move_traffic_bytes = 0;
+    s.t.h2d_copies = s.t.move_launches = s.t.verify_launches = s.t.feeds = 0;
+
+    // ---- what the gather launch copies, and what is in place once it has run
+    const size_t n = pl.ops.size();
+    std::vector<tgk::Copy> copies;
+    std::vector<u32> group0;
+    std::vector<FeedItem> missing;
+    try {
+        s.fed.assign(n, 1);
+        for (size_t k = 0; k < n; ++k) {
+            const tg::Op &op = pl.ops[k];
+            if (op.kind == 0) {
+                group0.push_back(u32(k));
+                if (!pl.alias) copies.push_back(tgk::Copy{base + op.dst_off, base + op.src_off, op.nbytes});
+            } else {
+                s.fed[k] = 0;
+                s.unfed += 1;
+                if (image) missing.push_back(FeedItem{u32(k), static_cast<const char *>(pl.host_base) + op.src_off});
+            }
+        }
+        if (image && !missing.empty()) {
+            // small missing tensors ride in the gather launch, read through the pinned
+            // image's device mapping, instead of one copy-engine call each
+            std::vector<u32> small_ops;
+            split_small(s, missing, pl.host_base, device_mapping(pl.host_base), copies, small_ops, *first_dma);
+            for (u32 k : small_ops) {
+                group0.push_back(k);
+                s.fed[k] = 1;
+                s.unfed -= 1;
+            }
+        }
+    } catch (...) {
+        return TG_ERR_NOMEM;
+    }
+    for (const auto &c : copies) s.t.gather_bytes += c.nbytes;
+
+    // ---- room for every table this load can need (the buffers cannot grow once a kernel reads them)
+    // results; the gather's and the moves' tables; two span tables; per missing tensor one
+    // feed at worst, each a dozen small tables padded to 256 bytes
+    size_t bound = 8192 + (n + pl.moves.size()) * 64 + copies.size() * 32 + (size_t(s.unfed) + first_dma_count(first_dma) + 1) * 4096;
+    for (const auto &rows : move_rows) bound += rows.size() * 32 + 1280;
+    if ((rc = pool->dev.ensure(bound)) != TG_OK) return rc;
+    s.cap = pool->dev.cap;
+    if (verify) {
+        s.results_cap = u32(n + pl.moves.size());
+        if ((rc = tab_alloc(s, size_t(s.results_cap) * sizeof(u64), &s.results_off)) != TG_OK) return rc;
+    }
+    s.uploaded = s.used;                                  // result words are cleared by a kernel, not uploaded
+
+    std::vector<CopyLaunch> move_launch(move_rows.size());
+    CopyLaunch gather;
+    FpLaunch fp_moved, fp_group0;
+    try {
+        for (size_t i = 0; i < move_rows.size(); ++i)
+            if ((rc = place_copy_launch(s, move_rows[i], move_launch[i])) != TG_OK) return rc;
+        if (!copies.empty() && (rc = place_copy_launch(s, copies, gather)) != TG_OK) return rc;
+        if (verify) {
+            if ((rc = place_verify(s, group0, false, fp_group0)) != TG_OK) return rc;
+            if (!pl.moves.empty() && (rc = place_verify(s, group0, true, fp_moved)) != TG_OK) return rc;
+        }
+    } catch (...) {
+        return TG_ERR_NOMEM;
+    }
+
+    // From here on work is enqueued: the session belongs to the plan, and a failure ends it.
+    guard.s = nullptr;
+    plan->session = sp;
+    plan->pool = pool;
+    pool->in_flight = plan;
+    auto enqueue = [&]() -> tg_status {
+        tg_status r;
+        if ((r = upload_tables(s)) != TG_OK) return r;
+        if (verify && s.results_cap > 0) {
+            tgk::zero_words_kernel<<<dim3((s.results_cap + 255) / 256), dim3(256), 0, s.sg>>>(
+                reinterpret_cast<u64 *>(tab_d(s) + s.results_off), s.results_cap);
+            TG_HIP(hipGetLastError());
+        }
+        // ---- moves first (stream A); nothing may land in the pool before they are done
+        if (!move_launch.empty()) {
+            if ((r = new_event(s, &s.move_ev.a)) != TG_OK || (r = new_event(s, &s.move_ev.b)) != TG_OK) return r;
+            if (s.prof) TG_HIP(hipEventRecord(s.move_ev.a, s.sg));
+            s.wrote = true;
+            for (const CopyLaunch &c : move_launch)
+                if ((r = launch_copy(s, c)) != TG_OK) return r;
+            TG_HIP(hipEventRecord(s.move_ev.b, s.sg));
+            if (s.sh != s.sg) TG_HIP(hipStreamWaitEvent(s.sh, s.move_ev.b, 0));
+            if (s.dual) TG_HIP(hipStreamWaitEvent(s.sh2, s.move_ev.b, 0));
+            s.timed_moves = s.prof;
+            s.t.move_bytes = pl.moved_bytes;
+            s.t.move_traffic_bytes = move_traffic;
+            s.t.move_launches = u32(move_launch.size());
+            if (verify && (r = launch_verify(s, fp_moved)) != TG_OK) return r;    // the moved tensors, where they are now
+        }
+        // ---- gather launch (stream A), then the fingerprint of what it wrote
+        if (gather.tiles > 0) {
+            if (s.prof) {
+                if ((r = new_event(s, &s.gather_ev.a)) != TG_OK || (r = new_event(s, &s.gather_ev.b)) != TG_OK) return r;
+                TG_HIP(hipEventRecord(s.gather_ev.a, s.sg));
+            }
+            s.wrote = true;
+            if ((r = launch_copy(s, gather)) != TG_OK) return r;
+            if (s.prof) {
+                TG_HIP(hipEventRecord(s.gather_ev.b, s.sg));
+                s.timed_gather = true;
+            }
+        }
+        if (verify && (r = launch_verify(s, fp_group0)) != TG_OK) return r;
+        return TG_OK;
+    };
+    rc = enqueue();
+    if (rc != TG_OK) return session_fail(plan, rc);
+    return TG_OK;
+}
+
+// One feed of an open load: rows checked by the caller.
+tg_status session_feed(Session &s, const void *seg_base, const std::vector<FeedItem> &items, bool small_allowed,
+                       bool may_block, uint32_t *ticket) {
+    tg_status rc;
+    std::vector<tgk::Copy> small_rows;
+    std::vector<u32> small_ops;
+    std::vector<FeedItem> dma;
+    if (small_allowed) split_small(s, items, seg_base, device_mapping(seg_base), small_rows, small_ops, dma);
+    else dma = items;
+    Session::Ticket tk{nullptr, nullptr};
+    if (!small_rows.empty()) {
+        CopyLaunch cl;
+        FpLaunch fp;
+        if ((rc = place_copy_launch(s, small_rows, cl)) != TG_OK) return rc;
+        if (s.verify && (rc = place_verify(s, small_ops, false, fp)) != TG_OK) return rc;
+        if ((rc = upload_tables(s)) != TG_OK) return rc;
+        s.wrote = true;
+        if ((rc = launch_copy(s, cl)) != TG_OK) return rc;
+        if ((rc = new_event(s, &tk.kernel)) != TG_OK) return rc;
+        TG_HIP(hipEventRecord(tk.kernel, s.sg));
+        if (s.verify && (rc = launch_verify(s, fp)) != TG_OK) return rc;
+        for (const auto &c : small_rows) s.t.gather_bytes += c.nbytes;
+    }
+    if ((rc = feed_transfers(s, dma, may_block, &tk.transfer)) != TG_OK) return rc;
+    for (const FeedItem &it : items) {
+        s.fed[it.k] = 1;
+        s.unfed -= 1;
+    }
+    s.t.feeds += 1;
+    s.tickets.push_back(tk);
+    if (ticket) *ticket = uint32_t(s.tickets.size() - 1);
+    return TG_OK;
+}
+
+// Ends a load: join, timings, integrity check, commit.
+tg_status session_wait(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
+    Session &s = *plan->session;
+    tg::ReuseStore &store = pool->store;
+    tg::Plan &pl = plan->plan;
+    if (s.unfed != 0) return session_fail(plan, TG_ERR_INVALID);
+    auto finish = [&]() -> tg_status {
+        if (s.verify && s.results_used > 0)
+            TG_HIP(hipMemcpyAsync(tab_h(s) + s.results_off, tab_d(s) + s.results_off, size_t(s.results_used) * sizeof(u64),
+                                  hipMemcpyDeviceToHost, s.sg));
+        // ---- join
+        TG_HIP(hipStreamSynchronize(s.sg));
+        if (s.sh != s.sg) TG_HIP(hipStreamSynchronize(s.sh));
+        if (s.dual) TG_HIP(hipStreamSynchronize(s.sh2));
+        if (s.prof) {
+            float ms = 0.f;
+            if (s.timed_gather) TG_HIP(hipEventElapsedTime(&ms, s.gather_ev.a, s.gather_ev.b));
+            s.t.gather_ms = ms;
+            ms = 0.f;
+            if (s.timed_moves) TG_HIP(hipEventElapsedTime(&ms, s.move_ev.a, s.move_ev.b));
+            s.t.move_ms = ms;
+            float total = 0.f;
+            for (const auto &ev : s.h2d_ev) {
+                TG_HIP(hipEventElapsedTime(&ms, ev.a, ev.b));
+                total += ms;
+            }
+            s.t.h2d_ms = total;
+            total = 0.f;
+            for (const auto &ev : s.verify_ev) {
+                TG_HIP(hipEventElapsedTime(&ms, ev.a, ev.b));
+                total += ms;
+            }
+            s.t.verify_ms = total;
+        }
+        // ---- the integrity check proper: every slot's fingerprint against its descriptor,
+        // every moved tensor's against its row of the Tensor Mapping
+        if (s.verify) {
+            const u64 *res = reinterpret_cast<const u64 *>(tab_h(s) + s.results_off);
+            bool good = true;
+            for (size_t i = 0; i < s.result_ref.size(); ++i) {
+                const int64_t ref = s.result_ref[i];
+                if (ref >= 0) {
+                    if (res[i] != pl.fps[size_t(ref)]) good = false;
+                } else {
+                    const tg::Move &m = pl.moves[size_t(-1 - ref)];
+                    if (res[i] != m.fp) { s.corrupt_moved.push_back(m.entry); good = false; }
+                }
+            }
+            if (!good) return TG_ERR_CORRUPT;
+        }
+        return TG_OK;
+    };
+    tg_status rc = finish();
+    if (rc != TG_OK) return session_fail(plan, rc);
+
+    // ---- commit (Section 3.1: update the mapping, return the addresses)
+    std::vector<uint64_t> dst;
+    const tg::Status cs = store.commit(pl, dst);
+    plan->timing = s.t;
+    pool->in_flight = nullptr;
+    plan->session = nullptr;
+    delete &s;
+    if (cs != tg::OK) return tg_status(cs);
+    if (out_dev_ptrs)
+        for (size_t k = 0; k < dst.size(); ++k)
+            out_dev_ptrs[k] = reinterpret_cast<void *>(uintptr_t(store.base() + dst[k]));
     return TG_OK;
 }
 
@@ -475,6 +1102,9 @@ tg_status tg_pool_create(void *dev_base, uint64_t capacity, uint32_t align, tg_p
 }
 
 tg_status tg_pool_destroy(tg_pool *pool) {
+    if (!pool) return TG_OK;
+    if (pool->in_flight) (void)session_fail(pool->in_flight, TG_ERR_INVALID);
+    pool->dev.shutdown();
     delete pool;
     return TG_OK;
 }
@@ -515,8 +1145,36 @@ tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint
     return TG_OK;
 }
 
-tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream) {
-    if (n == 0) return TG_OK;
+tg_status tg_default_tuning(tg_tuning *out) {
+    if (!out) return TG_ERR_INVALID;
+    *out = kDefaultTuning;
+    return TG_OK;
+}
+
+tg_status tg_pool_set_tuning(tg_pool *pool, const tg_tuning *t) {
+    if (!pool || !t || pool->in_flight) return TG_ERR_INVALID;
+    pool->tune = *t;
+    return TG_OK;
+}
+
+tg_status tg_pool_get_tuning(const tg_pool *pool, tg_tuning *out) {
+    if (!pool || !out) return TG_ERR_INVALID;
+    *out = pool->tune;
+    return TG_OK;
+}
+
+tg_status tg_pool_set_profiling(tg_pool *pool, int on) {
+    if (!pool || pool->in_flight) return TG_ERR_INVALID;
+    pool->profiling = on != 0;
+    return TG_OK;
+}
+
+tg_status tg_fingerprint_ex(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream,
+                            const tg_tuning *tuning, float *kernel_ms) {
+    if (n == 0) {
+        if (kernel_ms) *kernel_ms = 0.f;
+        return TG_OK;
+    }
     if (!spans || !out_fp) return TG_ERR_INVALID;
     for (u32 i = 0; i < n; ++i) {
         if (spans[i].nbytes != 0 && !spans[i].ptr) return TG_ERR_INVALID;
@@ -524,11 +1182,18 @@ tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, voi
     }
     std::vector<uint64_t> tmp;
     try { tmp.resize(n); } catch (...) { return TG_ERR_NOMEM; }
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    const tg_status rc = fingerprint_locked(spans, n, tmp.data(), static_cast<hipStream_t>(stream),
-                                            &g_timing.fingerprint_ms, &g_timing.fingerprint_bytes);
-    if (rc == TG_OK) std::memcpy(out_fp, tmp.data(), n * sizeof(uint64_t));
-    return rc;
+    float ms = 0.f;
+    std::lock_guard<std::mutex> lock(g_shared.mu);
+    const tg_status rc = fingerprint_run(g_shared.t, tuning ? *tuning : kDefaultTuning, spans, n, tmp.data(),
+                                         static_cast<hipStream_t>(stream), kernel_ms ? &ms : nullptr);
+    if (rc != TG_OK) return rc;
+    std::memcpy(out_fp, tmp.data(), n * sizeof(uint64_t));
+    if (kernel_ms) *kernel_ms = ms;
+    return TG_OK;
+}
+
+tg_status tg_fingerprint(const tg_span *spans, uint32_t n, uint64_t *out_fp, void *stream) {
+    return tg_fingerprint_ex(spans, n, out_fp, stream, nullptr, nullptr);
 }
 
 // tg_fingerprint for callers that may not allocate: the span table, the tile
@@ -586,8 +1251,12 @@ tg_status tg_fingerprint_noalloc(const tg_span *spans, uint32_t n, uint64_t *out
     return TG_OK;
 }
 
-tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, void *stream) {
-    if (n == 0) return TG_OK;
+tg_status tg_compare_ex(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, void *stream,
+                        const tg_tuning *tuning, float *kernel_ms) {
+    if (n == 0) {
+        if (kernel_ms) *kernel_ms = 0.f;
+        return TG_OK;
+    }
     if (!pairs || !out_differs) return TG_ERR_INVALID;
     for (u32 i = 0; i < n; ++i) {
         if (pairs[i].nbytes != 0 && (!pairs[i].a || !pairs[i].b)) return TG_ERR_INVALID;
@@ -595,10 +1264,18 @@ tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, vo
     }
     std::vector<uint32_t> tmp;
     try { tmp.resize(n); } catch (...) { return TG_ERR_NOMEM; }
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    const tg_status rc = compare_locked(pairs, n, tmp.data(), static_cast<hipStream_t>(stream));
-    if (rc == TG_OK) std::memcpy(out_differs, tmp.data(), n * sizeof(uint32_t));
-    return rc;
+    float ms = 0.f;
+    std::lock_guard<std::mutex> lock(g_shared.mu);
+    const tg_status rc = compare_run(g_shared.t, tuning ? *tuning : kDefaultTuning, pairs, n, tmp.data(),
+                                     static_cast<hipStream_t>(stream), kernel_ms ? &ms : nullptr);
+    if (rc != TG_OK) return rc;
+    std::memcpy(out_differs, tmp.data(), n * sizeof(uint32_t));
+    if (kernel_ms) *kernel_ms = ms;
+    return TG_OK;
+}
+
+tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, void *stream) {
+    return tg_compare_ex(pairs, n, out_differs, stream, nullptr, nullptr);
 }
 
 tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
@@ -613,11 +1290,13 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
     tg::ReuseStore &store = pool->store;
     if (store.model_active(model->model_id)) return TG_ERR_INVALID;
     const bool confirm = (flags & TG_PLAN_CONFIRM) != 0;
-    if (confirm && !model->host_base) return TG_ERR_INVALID;
+    if (confirm && (!model->host_base || pool->in_flight)) return TG_ERR_INVALID;
 
     const size_t n = tensors.size();
     std::vector<uint64_t> hits(n, 0);
     std::vector<std::pair<uint64_t, uint64_t>> cand;      // (offset, entry id), ascending offset
+    float compare_ms = 0.f;
+    uint64_t compare_bytes = 0;
     if (!confirm) {
         // Section 3.1: a tensor found in the Tensor Mapping is reused.
         for (size_t k = 0; k < n; ++k) {
@@ -627,11 +1306,8 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
     } else {
         // Every candidate of every tensor is compared with the incoming bytes
         // in one launch; the first candidate (lowest offset) that is equal wins.
-        void *host_dev = nullptr;
-        if (hipHostGetDevicePointer(&host_dev, const_cast<void *>(model->host_base), 0) != hipSuccess) {
-            (void)hipGetLastError();
-            return TG_ERR_INVALID;
-        }
+        void *host_dev = device_mapping(model->host_base);
+        if (!host_dev) return TG_ERR_INVALID;
         std::vector<tg_pair> pairs;
         std::vector<std::pair<size_t, uint64_t>> who;   // (tensor, candidate entry)
         for (size_t k = 0; k < n; ++k) {
@@ -644,12 +1320,13 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
                 if (!aligned16(p.b)) return TG_ERR_INVALID;
                 pairs.push_back(p);
                 who.push_back({k, c.second});
+                compare_bytes += p.nbytes;
             }
         }
         if (!pairs.empty()) {
             std::vector<uint32_t> differs(pairs.size());
-            std::lock_guard<std::mutex> lock(g_scratch.mu);
-            rc = compare_locked(pairs.data(), u32(pairs.size()), differs.data(), static_cast<hipStream_t>(stream));
+            rc = compare_run(pool->dev, pool->tune, pairs.data(), u32(pairs.size()), differs.data(),
+                             static_cast<hipStream_t>(stream), pool->profiling ? &compare_ms : nullptr);
             if (rc != TG_OK) return rc;
             for (size_t i = 0; i < pairs.size(); ++i)
                 if (!differs[i] && hits[who[i].first] == 0) hits[who[i].first] = who[i].second;
@@ -658,6 +1335,7 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
 
     tg_load_plan *lp = new (std::nothrow) tg_load_plan();
     if (!lp) return TG_ERR_NOMEM;
+    lp->pool = pool;
     lp->plan.model_id = model->model_id;
     lp->plan.host_base = model->host_base;
     lp->plan.host_bytes = model->host_bytes;
@@ -673,10 +1351,10 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
         const tg::Move &m = lp->plan.moves[i];
         lp->move_rows[i] = tg_move{m.old_off, m.new_off, m.nbytes};
     }
+    lp->timing.compare_ms = compare_ms;
+    lp->timing.compare_bytes = compare_bytes;
+    lp->timing.plan_host_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
     *out = lp;
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    if (g_profiling)
-        g_timing.plan_host_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
     return TG_OK;
 }
 
@@ -723,10 +1401,20 @@ tg_status tg_plan_evictions(const tg_load_plan *plan, const uint64_t **offsets, 
     return TG_OK;
 }
 
-void tg_plan_free(tg_load_plan *plan) { delete plan; }
+tg_status tg_plan_timing(const tg_load_plan *plan, tg_timing *out) {
+    if (!plan || !out) return TG_ERR_INVALID;
+    *out = plan->session ? plan->session->t : plan->timing;
+    return TG_OK;
+}
+
+void tg_plan_free(tg_load_plan *plan) {
+    if (!plan) return;
+    if (plan->session) (void)session_fail(plan, TG_ERR_INVALID);
+    delete plan;
+}
 
 tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
-    if (!pool || !plan) return TG_ERR_INVALID;
+    if (!pool || !plan || pool->in_flight) return TG_ERR_INVALID;
     std::vector<uint64_t> dst;
     const tg::Status s = pool->store.commit(plan->plan, dst);
     if (s != tg::OK) return tg_status(s);
@@ -737,8 +1425,94 @@ tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
 }
 
 tg_status tg_abandon(tg_pool *pool, tg_load_plan *plan) {
-    if (!pool || !plan) return TG_ERR_INVALID;
+    if (!pool || !plan || pool->in_flight) return TG_ERR_INVALID;
     return tg_status(pool->store.abandon(plan->plan));
+}
+
+tg_status tg_assemble_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args) {
+    return session_begin(pool, plan, args, false, nullptr);
+}
+
+// Starts a load from the plan's whole host image.  may_block: the caller is
+// about to wait anyway, so a small transfer may be joined by the host.
+static tg_status begin_from_image(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args, bool may_block) {
+    std::vector<FeedItem> dma;
+    tg_status rc = session_begin(pool, plan, args, true, &dma);
+    if (rc != TG_OK) return rc;
+    if (!dma.empty()) {
+        rc = session_feed(*plan->session, plan->plan.host_base, dma, false, may_block, nullptr);
+        if (rc != TG_OK) return session_fail(plan, rc);
+    }
+    return TG_OK;
+}
+
+tg_status tg_assemble_async(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args) {
+    return begin_from_image(pool, plan, args, false);
+}
+
+tg_status tg_assemble_feed(tg_pool *pool, tg_load_plan *plan, const void *seg_base, uint64_t seg_bytes,
+                           const tg_feed_row *rows, uint32_t n, uint32_t *ticket) {
+    if (!pool || !plan || !plan->session || pool->in_flight != plan) return TG_ERR_INVALID;
+    if (n == 0 || !rows || !seg_base) return TG_ERR_INVALID;
+    Session &s = *plan->session;
+    const tg::Plan &pl = plan->plan;
+    std::vector<FeedItem> items;
+    std::vector<char> seen;
+    try {
+        items.reserve(n);
+        seen.assign(pl.ops.size(), 0);
+    } catch (...) {
+        return TG_ERR_NOMEM;
+    }
+    for (u32 i = 0; i < n; ++i) {
+        const tg_feed_row &r = rows[i];
+        if (r.reserved != 0 || r.tensor >= pl.ops.size()) return TG_ERR_INVALID;
+        const tg::Op &op = pl.ops[r.tensor];
+        if (op.kind != 1 || s.fed[r.tensor] || seen[r.tensor]) return TG_ERR_INVALID;
+        if (r.seg_off > seg_bytes || op.nbytes > seg_bytes - r.seg_off) return TG_ERR_INVALID;
+        seen[r.tensor] = 1;
+        items.push_back(FeedItem{r.tensor, static_cast<const char *>(seg_base) + r.seg_off});
+    }
+    uint32_t tk = 0;
+    tg_status rc;
+    try {
+        rc = session_feed(s, seg_base, items, true, false, &tk);
+    } catch (...) {
+        rc = TG_ERR_NOMEM;
+    }
+    if (rc != TG_OK) return session_fail(plan, rc);
+    if (ticket) *ticket = tk;
+    return TG_OK;
+}
+
+tg_status tg_assemble_feed_wait(tg_pool *pool, tg_load_plan *plan, uint32_t ticket) {
+    if (!pool || !plan || !plan->session || pool->in_flight != plan) return TG_ERR_INVALID;
+    Session &s = *plan->session;
+    if (ticket >= s.tickets.size()) return TG_ERR_INVALID;
+    const Session::Ticket tk = s.tickets[ticket];
+    if (tk.kernel && hipEventSynchronize(tk.kernel) != hipSuccess) return session_fail(plan, TG_ERR_HIP);
+    if (tk.transfer && hipEventSynchronize(tk.transfer) != hipSuccess) return session_fail(plan, TG_ERR_HIP);
+    return TG_OK;
+}
+
+tg_status tg_assemble_wait(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
+    if (!pool || !plan || !plan->session || pool->in_flight != plan) return TG_ERR_INVALID;
+    try {
+        return session_wait(pool, plan, out_dev_ptrs);
+    } catch (...) {
+        return session_fail(plan, TG_ERR_NOMEM);
+    }
+}
+
+tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args, void **out_dev_ptrs) {
+    tg_status rc;
+    try {
+        rc = begin_from_image(pool, plan, args, true);
+    } catch (...) {
+        rc = plan && plan->session ? session_fail(plan, TG_ERR_NOMEM) : TG_ERR_NOMEM;
+    }
+    if (rc != TG_OK) return rc;
+    return tg_assemble_wait(pool, plan, out_dev_ptrs);
 }
 
 tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *stream_gather,
@@ -752,407 +1526,8 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     return tg_assemble_ex(pool, plan, &args, out_dev_ptrs);
 }
 
-tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args, void **out_dev_ptrs) {
-    if (!pool || !plan || !args) return TG_ERR_INVALID;
-    if (args->flags & ~TG_ASSEMBLE_VERIFY) return TG_ERR_INVALID;
-    const uint32_t flags = args->flags;
-    void *stream_gather = args->stream_gather, *stream_h2d = args->stream_h2d;
-    tg::ReuseStore &store = pool->store;
-    tg::Plan &pl = plan->plan;
-    if (pl.consumed || pl.pool_tag != &store) return TG_ERR_INVALID;
-    if (pl.generation != store.generation()) return TG_ERR_STALE;
-    if (store.model_active(pl.model_id)) return TG_ERR_INVALID;
-    if (pl.transfer_bytes > 0 && !pl.host_base) return TG_ERR_INVALID;
-    hipStream_t sg = static_cast<hipStream_t>(stream_gather), sh = static_cast<hipStream_t>(stream_h2d);
-    // The copies may be dealt over two streams: one copy then starts while the other is still
-    // running, which hides what a copy costs to start (about 10 us each on one stream).
-    hipStream_t sh2 = args->use_second_h2d_stream ? static_cast<hipStream_t>(args->stream_h2d_second) : sh;
-    const bool dual = sh2 != sh && sh2 != sg && sh != sg;
-    if (!dual) sh2 = sh;
-    const uint64_t base = store.base();
-    {
-        const tg_status rc = validate_plan(pl, store);
-        if (rc != TG_OK) return rc;
-    }
-
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    {
-        const tg_status rc = g_scratch.init();
-        if (rc != TG_OK) return rc;
-    }
-
-    // ---- merge moves (Section 3.2, Stage 2), cut into launches whose reads and
-    // writes do not meet
-    std::vector<std::vector<tgk::Copy>> launches;
-    u64 move_traffic = 0;
-    if (!pl.moves.empty()) {
-        tg_status rc = g_scratch.ensure_bounce();
-        if (rc != TG_OK) return rc;
-        rc = build_move_launches(pl.moves, base, launches, move_traffic);
-        if (rc != TG_OK) return rc;
-        rc = check_move_launches(launches, base, store.capacity());
-        if (rc != TG_OK) return rc;
-    }
-    const size_t n_move_launches = launches.size();
-
-    // Host-to-device list, in destination order; copies adjacent on both sides
-    // (the slot padding included) are merged into one (Section 4 groups
-    // adjacent tensors into large copies).
-    struct H2D { uint64_t dst, src, len, padded; std::vector<u32> ops; };
-    std::vector<H2D> h2d;
-    std::vector<tgk::Copy> copies;
-    const bool verify = (flags & TG_ASSEMBLE_VERIFY) != 0;
-    // Verification groups: spans to fingerprint once the bytes are in place.
-    // Group 0 holds what the gather launch writes (and aliased hits, already
-    // in place); the host-to-device copies are cut into a few batches, each
-    // verified on stream A as soon as its copies are done on stream B, so only
-    // the last batch's fingerprint is left when the transfer ends.
-    // A last group, if the plan moves resident tensors, holds those at their new
-    // addresses (`moved`: its rows are pl.moves, not pl.ops).
-    struct FpGroup {
-        std::vector<u32> ops;
-        bool moved = false;
-        size_t desc_off = 0, prefix_off = 0, result_off = 0;
-        u32 tiles = 0;
-        u64 bytes = 0;
-    };
-    std::vector<FpGroup> groups(1);
-    void *host_dev = nullptr;
-    const uint64_t small = g_tune.h2d_kernel_max_bytes;
-    if (small > 0 && pl.host_base &&
-        hipHostGetDevicePointer(&host_dev, const_cast<void *>(pl.host_base), 0) != hipSuccess) {
-        (void)hipGetLastError();
-        host_dev = nullptr;
-    }
-    for (size_t k = 0; k < pl.ops.size(); ++k) {
-        const tg::Op &op = pl.ops[k];
-        if (op.kind == 0) {
-            groups[0].ops.push_back(u32(k));
-            if (pl.alias) continue;                      // used where it lies: nothing to copy
-            copies.push_back(tgk::Copy{base + op.dst_off, base + op.src_off, op.nbytes});
-        } else if (host_dev && op.nbytes <= small &&
-                   ((uintptr_t(host_dev) + op.src_off) & 15u) == 0) {
-            // small missing tensors ride in the gather launch, read through the
-            // pinned buffer's device mapping, instead of one DMA call each
-            groups[0].ops.push_back(u32(k));
-            copies.push_back(tgk::Copy{base + op.dst_off, u64(uintptr_t(host_dev)) + op.src_off, op.nbytes});
-        } else {
-            h2d.push_back(H2D{op.dst_off, op.src_off, op.nbytes, store.round_up(op.nbytes), {u32(k)}});
-        }
-    }
-    std::sort(h2d.begin(), h2d.end(), [](const H2D &a, const H2D &b) { return a.dst < b.dst; });
-    std::vector<H2D> merged;
-    u64 h2d_total = 0;
-    for (const H2D &c : h2d) {
-        h2d_total += c.len;
-        if (!merged.empty()) {
-            H2D &m = merged.back();
-            if (m.dst + m.padded == c.dst && m.src + m.padded == c.src) {
-                m.len = m.padded + c.len;
-                m.padded += c.padded;
-                m.ops.push_back(c.ops[0]);
-                continue;
-            }
-        }
-        merged.push_back(c);
-    }
-    // batch_end[j] = index one past the last merged copy of batch j
-    std::vector<size_t> batch_end;
-    if (!merged.empty()) {
-        const size_t nb = !verify ? 1 : std::max<size_t>(1, std::min<size_t>(
-            std::min<size_t>(kVerifyBatches, merged.size()), size_t(h2d_total / kVerifyBatchMinBytes)));
-        // shares nb : nb-1 : ... : 1, so that little is left to fingerprint when the last copy lands
-        const u64 denom = u64(nb) * (nb + 1) / 2;
-        u64 acc = 0, cum = nb;
-        for (size_t i = 0; i < merged.size(); ++i) {
-            acc += merged[i].len;
-            const size_t done = batch_end.size();
-            if (i + 1 == merged.size() || (done + 1 < nb && acc * denom >= h2d_total * cum)) {
-                batch_end.push_back(i + 1);
-                cum += nb - (done + 1);
-            }
-        }
-        if (verify) {
-            size_t from = 0;
-            for (size_t e : batch_end) {
-                FpGroup g;
-                for (size_t i = from; i < e; ++i) g.ops.insert(g.ops.end(), merged[i].ops.begin(), merged[i].ops.end());
-                groups.push_back(std::move(g));
-                from = e;
-            }
-        }
-    }
-    const size_t moved_group = groups.size();           // index of the moved tensors' group, if there is one
-    if (verify && !pl.moves.empty()) {
-        FpGroup g;
-        g.moved = true;
-        groups.push_back(std::move(g));
-    }
-    auto rows_of = [&](const FpGroup &g) { return g.moved ? pl.moves.size() : g.ops.size(); };
-    u64 gather_bytes = 0;
-    for (const auto &c : copies) gather_bytes += c.nbytes;
-    if (!copies.empty()) launches.push_back(copies);
-
-    // ---- one table upload for every launch of this call
-    const u32 U = pick_u(g_tune.gather_unroll);
-    const u64 tile = tile_for(tgk::kCopyThreads, U);
-    const u32 FU = pick_u(g_tune.fingerprint_unroll);
-    const u64 fp_tile = tile_for(tgk::kReadThreads, FU);
-    struct Placed { size_t desc_off, prefix_off, ticket_off; u32 n, tiles; };
-    std::vector<Placed> placed(launches.size());
-    size_t table_bytes = 0;
-    for (size_t i = 0; i < launches.size(); ++i) {
-        const TableLayout L = table_layout(launches[i].size(), sizeof(tgk::Copy), 0);
-        placed[i].desc_off = table_bytes + L.desc_off;
-        placed[i].prefix_off = table_bytes + L.prefix_off;
-        placed[i].ticket_off = table_bytes + L.total;    // the launch's tile counter, uploaded as zero
-        placed[i].n = u32(launches[i].size());
-        table_bytes += L.total + 256;
-    }
-    size_t results_off = 0, results_words = 0;
-    if (verify) {
-        for (FpGroup &g : groups) {
-            const TableLayout L = table_layout(rows_of(g), sizeof(tgk::Span), 0);
-            g.desc_off = table_bytes + L.desc_off;
-            g.prefix_off = table_bytes + L.prefix_off;
-            table_bytes += L.total;
-        }
-        results_off = table_bytes;                       // one result word per tensor, group after group
-        for (FpGroup &g : groups) {
-            g.result_off = results_off + results_words * sizeof(u64);
-            results_words += rows_of(g);
-        }
-        table_bytes += align_up(results_words * sizeof(u64), 256);
-    }
-    DrainOnExit drain_gather(sg);
-    drain_gather.armed = false;                 // nothing enqueued yet
-    if (table_bytes > 0) {
-        tg_status rc = g_scratch.ensure(table_bytes);
-        if (rc != TG_OK) return rc;
-        char *h = static_cast<char *>(g_scratch.h);
-        for (size_t i = 0; i < launches.size(); ++i) {
-            std::memcpy(h + placed[i].desc_off, launches[i].data(), launches[i].size() * sizeof(tgk::Copy));
-            u32 *hp = reinterpret_cast<u32 *>(h + placed[i].prefix_off);
-            if (!fill_prefix(hp, &launches[i][0].nbytes, sizeof(tgk::Copy) / 8, launches[i].size(), tile))
-                return TG_ERR_INVALID;
-            placed[i].tiles = hp[launches[i].size()];
-            std::memset(h + placed[i].ticket_off, 0, 256);
-        }
-        if (verify) {
-            for (FpGroup &g : groups) {
-                const size_t rows = rows_of(g);
-                if (rows == 0) continue;
-                tgk::Span *hs = reinterpret_cast<tgk::Span *>(h + g.desc_off);
-                for (size_t i = 0; i < rows; ++i) {
-                    hs[i].ptr = base + (g.moved ? pl.moves[i].new_off : pl.ops[g.ops[i]].dst_off);
-                    hs[i].nbytes = g.moved ? pl.moves[i].nbytes : pl.ops[g.ops[i]].nbytes;
-                    g.bytes += hs[i].nbytes;
-                }
-                u32 *hp = reinterpret_cast<u32 *>(h + g.prefix_off);
-                if (!fill_prefix(hp, &hs[0].nbytes, sizeof(tgk::Span) / 8, rows, fp_tile)) return TG_ERR_INVALID;
-                g.tiles = hp[rows];
-            }
-        }
-        TG_HIP(hipMemcpyAsync(g_scratch.d, g_scratch.h, verify ? results_off : table_bytes,
-                              hipMemcpyHostToDevice, sg));
-        drain_gather.armed = true;
-        if (verify && results_words > 0) {
-            tgk::zero_words_kernel<<<dim3(u32((results_words + 255) / 256)), dim3(256), 0, sg>>>(
-                reinterpret_cast<u64 *>(static_cast<char *>(g_scratch.d) + results_off), u32(results_words));
-            TG_HIP(hipGetLastError());
-        }
-    }
-    auto launch_copy = [&](size_t i) -> tg_status {
-        if (placed[i].tiles == 0) return TG_OK;
-        char *d = static_cast<char *>(g_scratch.d);
-        const u32 grid = grid_for(placed[i].tiles, g_tune.gather_wgs_per_cu);
-        TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU><<<dim3(grid), dim3(tgk::kCopyThreads), 0, sg>>>(
-                        reinterpret_cast<const tgk::Copy *>(d + placed[i].desc_off),
-                        reinterpret_cast<const u32 *>(d + placed[i].prefix_off), placed[i].n,
-                        reinterpret_cast<u32 *>(d + placed[i].ticket_off)));
-        TG_HIP(hipGetLastError());
-        return TG_OK;
-    };
-    // fingerprint of verification group gi on stream A (events 6+2gi, 7+2gi time it)
-    auto launch_verify = [&](size_t gi) -> tg_status {
-        const FpGroup &g = groups[gi];
-        if (g.tiles == 0) return TG_OK;
-        char *d = static_cast<char *>(g_scratch.d);
-        const u32 grid = grid_for(g.tiles, g_tune.fingerprint_wgs_per_cu);
-        const u32 run = run_for(g.tiles, grid);
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[6 + 2 * gi], sg));
-        TG_FOR_U(FU, tgk::fingerprint_kernel<tgk::kReadThreads, kU><<<dim3(grid), dim3(tgk::kReadThreads), 0, sg>>>(
-                         reinterpret_cast<const tgk::Span *>(d + g.desc_off),
-                         reinterpret_cast<const u32 *>(d + g.prefix_off), u32(rows_of(g)), run,
-                         reinterpret_cast<u64 *>(d + g.result_off)));
-        TG_HIP(hipGetLastError());
-        if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[7 + 2 * gi], sg));
-        return TG_OK;
-    };
-
-    // Everything that touches the pool's bytes: once this has started, a
-    // failure may leave some of the plan's writes done.
-    std::vector<uint64_t> corrupt_moved;                  // moved tensors that no longer match their rows
-    auto device_work = [&]() -> tg_status {
-        // ---- moves first (stream A); nothing may land in the pool before they are done
-        if (n_move_launches > 0) {
-            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[4], sg));
-            for (size_t i = 0; i < n_move_launches; ++i) {
-                const tg_status rc = launch_copy(i);
-                if (rc != TG_OK) return rc;
-            }
-            TG_HIP(hipEventRecord(g_scratch.ev[5], sg));
-            if (sh != sg) TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[5], 0));
-            if (dual) TG_HIP(hipStreamWaitEvent(sh2, g_scratch.ev[5], 0));
-            if (verify) {                                 // the moved tensors, where they are now
-                const tg_status rc = launch_verify(moved_group);
-                if (rc != TG_OK) return rc;
-            }
-        }
-
-        // ---- gather launch (stream A), then the fingerprint of what it wrote
-        if (!copies.empty()) {
-            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[0], sg));
-            const tg_status rc = launch_copy(launches.size() - 1);
-            if (rc != TG_OK) return rc;
-            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[1], sg));
-        }
-        if (verify) {
-            const tg_status rc = launch_verify(0);
-            if (rc != TG_OK) return rc;
-        }
-
-        // ---- host-to-device copies (stream B), overlapped with the gather; each
-        // batch is fingerprinted on stream A as soon as it has landed
-        u64 h2d_bytes = 0;
-        if (!merged.empty()) {
-            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[2], sh));
-            size_t from = 0;
-            for (size_t j = 0; j < batch_end.size(); ++j) {
-                bool used2 = false;
-                for (size_t i = from; i < batch_end[j]; ++i) {
-                    const H2D &c = merged[i];
-                    const bool second = dual && (i & 1) != 0;
-                    TG_HIP(hipMemcpyAsync(reinterpret_cast<void *>(uintptr_t(base + c.dst)),
-                                          static_cast<const char *>(pl.host_base) + c.src, c.len,
-                                          hipMemcpyHostToDevice, second ? sh2 : sh));
-                    used2 = used2 || second;
-                    h2d_bytes += c.len;
-                }
-                from = batch_end[j];
-                if (verify) {
-                    if (sh != sg && h2d_total < kVerifyBatchMinBytes) {
-                        TG_HIP(hipStreamSynchronize(sh));        // small transfer: the host joins
-                        if (used2) TG_HIP(hipStreamSynchronize(sh2));
-                    } else if (sh != sg) {
-                        TG_HIP(hipEventRecord(g_scratch.ev[kBatchEvent0 + j], sh));
-                        TG_HIP(hipStreamWaitEvent(sg, g_scratch.ev[kBatchEvent0 + j], 0));
-                        if (used2) {
-                            TG_HIP(hipEventRecord(g_scratch.ev[kBatch2Event0 + j], sh2));
-                            TG_HIP(hipStreamWaitEvent(sg, g_scratch.ev[kBatch2Event0 + j], 0));
-                        }
-                    }
-                    const tg_status rc = launch_verify(1 + j);
-                    if (rc != TG_OK) return rc;
-                }
-            }
-            if (dual) {                                   // stream B's end event covers the second stream
-                TG_HIP(hipEventRecord(g_scratch.ev[kSecondDoneEvent], sh2));
-                TG_HIP(hipStreamWaitEvent(sh, g_scratch.ev[kSecondDoneEvent], 0));
-            }
-            if (g_profiling) TG_HIP(hipEventRecord(g_scratch.ev[3], sh));
-        }
-        if (verify && results_words > 0)
-            TG_HIP(hipMemcpyAsync(static_cast<char *>(g_scratch.h) + results_off,
-                                  static_cast<char *>(g_scratch.d) + results_off, results_words * sizeof(u64),
-                                  hipMemcpyDeviceToHost, sg));
-
-        // ---- join
-        TG_HIP(hipStreamSynchronize(sg));
-        if (sh != sg) TG_HIP(hipStreamSynchronize(sh));
-        if (dual) TG_HIP(hipStreamSynchronize(sh2));
-        if (g_profiling) {
-            float ms = 0.f;
-            if (!copies.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[0], g_scratch.ev[1]));
-            g_timing.gather_ms = ms;
-            g_timing.gather_bytes = gather_bytes;
-            ms = 0.f;
-            if (!merged.empty()) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[2], g_scratch.ev[3]));
-            g_timing.h2d_ms = ms;
-            g_timing.h2d_bytes = h2d_bytes;
-            g_timing.h2d_copies = u32(merged.size());
-            ms = 0.f;
-            if (n_move_launches > 0) TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[4], g_scratch.ev[5]));
-            g_timing.move_ms = ms;
-            g_timing.move_bytes = pl.moved_bytes;
-            g_timing.move_traffic_bytes = move_traffic;
-            g_timing.move_launches = u32(n_move_launches);
-            if (verify) {
-                float total = 0.f;
-                u64 bytes = 0;
-                u32 launched = 0;
-                for (size_t gi = 0; gi < groups.size(); ++gi) {
-                    if (groups[gi].tiles == 0) continue;
-                    TG_HIP(hipEventElapsedTime(&ms, g_scratch.ev[6 + 2 * gi], g_scratch.ev[7 + 2 * gi]));
-                    total += ms;
-                    bytes += groups[gi].bytes;
-                    ++launched;
-                }
-                g_timing.verify_ms = total;
-                g_timing.verify_bytes = bytes;
-                g_timing.verify_launches = launched;
-            }
-        }
-
-        // ---- the integrity check proper: every slot's fingerprint against its descriptor,
-        // every moved tensor's against its row of the Tensor Mapping
-        if (verify) {
-            const u64 *res = reinterpret_cast<const u64 *>(static_cast<char *>(g_scratch.h) + results_off);
-            size_t at = 0;
-            bool good = true;
-            for (const FpGroup &g : groups) {
-                if (g.moved) {
-                    for (const tg::Move &m : pl.moves)
-                        if (res[at++] != m.fp) { corrupt_moved.push_back(m.entry); good = false; }
-                } else {
-                    for (u32 k : g.ops)
-                        if (res[at++] != pl.fps[k]) good = false;
-                }
-            }
-            if (!good) return TG_ERR_CORRUPT;
-        }
-        return TG_OK;
-    };
-    {
-        const tg_status rc = device_work();
-        if (rc != TG_OK) {
-            // nothing of this call may still be running when the tables are reused
-            (void)hipStreamSynchronize(sg);
-            if (sh != sg) (void)hipStreamSynchronize(sh);
-            if (dual) (void)hipStreamSynchronize(sh2);
-            (void)hipGetLastError();
-            // evicted tensors may have been overwritten and moved ones have moved:
-            // record that much, so that the mapping describes the pool's bytes
-            if (!pl.moves.empty() || !pl.evict.empty()) (void)store.abandon(pl);
-            store.drop_corrupt(corrupt_moved);
-            return rc;
-        }
-    }
-
-    drain_gather.armed = false;                 // both streams have been waited for
-
-    // ---- commit (Section 3.1: update the mapping, return the addresses)
-    std::vector<uint64_t> dst;
-    const tg::Status s = store.commit(pl, dst);
-    if (s != tg::OK) return tg_status(s);
-    if (out_dev_ptrs)
-        for (size_t k = 0; k < dst.size(); ++k)
-            out_dev_ptrs[k] = reinterpret_cast<void *>(uintptr_t(base + dst[k]));
-    return TG_OK;
-}
-
 tg_status tg_release(tg_pool *pool, uint64_t model_id, uint32_t flags) {
-    if (!pool) return TG_ERR_INVALID;
+    if (!pool || pool->in_flight) return TG_ERR_INVALID;
     return tg_status(pool->store.release(model_id, (flags & TG_RELEASE_EVICT) != 0));
 }
 
@@ -1177,33 +1552,6 @@ tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double 
     return TG_OK;
 }
 
-void tg_set_profiling(int on) {
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    g_profiling = on != 0;
-    g_timing = tg_timing{};
-}
-
-tg_status tg_last_timing(tg_timing *out) {
-    if (!out) return TG_ERR_INVALID;
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    *out = g_timing;
-    return TG_OK;
-}
-
-tg_status tg_set_tuning(const tg_tuning *t) {
-    if (!t) return TG_ERR_INVALID;
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    g_tune = *t;
-    return TG_OK;
-}
-
-tg_status tg_get_tuning(tg_tuning *t) {
-    if (!t) return TG_ERR_INVALID;
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    *t = g_tune;
-    return TG_OK;
-}
-
 tg_status tg_host_alloc(uint64_t nbytes, void **out) {
     if (!out || nbytes == 0) return TG_ERR_INVALID;
     void *p = nullptr;
@@ -1221,9 +1569,42 @@ tg_status tg_host_free(void *p) {
     return TG_OK;
 }
 
+tg_status tg_measure_mix_rate(uint32_t iters, void *stream, double *words_per_s) {
+    if (!words_per_s || iters == 0 || iters > (1u << 20)) return TG_ERR_INVALID;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g_shared.mu);
+    DeviceTables &T = g_shared.t;
+    tg_status rc = T.ensure(4096);
+    if (rc != TG_OK) return rc;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if ((rc = T.event(0, &e0)) != TG_OK || (rc = T.event(1, &e1)) != TG_OK) return rc;
+    const u32 grid = u32(T.cu_count) * 8;
+    DrainOnExit drain(st);
+    TG_HIP(hipEventRecord(e0, st));
+    tgk::mix_rate_kernel<tgk::kReadThreads><<<dim3(grid), dim3(tgk::kReadThreads), 0, st>>>(
+        static_cast<u64 *>(T.d), iters, 0x9E3779B97F4A7C15ull);
+    TG_HIP(hipGetLastError());
+    TG_HIP(hipEventRecord(e1, st));
+    TG_HIP(hipStreamSynchronize(st));
+    drain.armed = false;
+    float ms = 0.f;
+    TG_HIP(hipEventElapsedTime(&ms, e0, e1));
+    if (!(ms > 0.f)) return TG_ERR_HIP;
+    *words_per_s = double(grid) * tgk::kReadThreads * double(iters) * 16.0 / (double(ms) * 1e-3);
+    return TG_OK;
+}
+
+tg_status tg_host_device_ptr(const void *pinned, void **out_dev) {
+    if (!pinned || !out_dev) return TG_ERR_INVALID;
+    void *dev = device_mapping(pinned);
+    if (!dev) return TG_ERR_INVALID;
+    *out_dev = dev;
+    return TG_OK;
+}
+
 void tg_shutdown(void) {
-    std::lock_guard<std::mutex> lock(g_scratch.mu);
-    g_scratch.shutdown();
+    std::lock_guard<std::mutex> lock(g_shared.mu);
+    g_shared.t.shutdown();
 }
 
 const char *tg_strerror(tg_status s) {

@@ -50,13 +50,20 @@ def _host_view(host) -> Tuple[torch.Tensor, int, int]:
 
 
 class RegisteredModel:
-    """A model in the CPU-side Model Cache: pinned bytes + per-tensor rows."""
+    """A model known to the Reuse Store: per-tensor rows and, if the whole model
+    fits the CPU-side Model Cache, its pinned image.  With ``host=None`` only
+    the rows exist (``offs`` are then the caller's own references) and the
+    missing tensors of a load are handed over segment by segment
+    (ReusePool.load_streamed)."""
 
     def __init__(self, model_id: int, host, offs: Sequence[int], sizes: Sequence[int],
                  fps: Sequence[int]):
         self.model_id = model_id
         self.host = host                       # keeps the pinned memory alive
-        self.host_tensor, ptr, length = _host_view(host)
+        if host is None:
+            self.host_tensor, ptr, length = None, 0, 0
+        else:
+            self.host_tensor, ptr, length = _host_view(host)
         self.offs = list(offs)
         self.sizes = list(sizes)
         self.fps = list(fps)
@@ -228,6 +235,13 @@ class ReusePool:
         self.stream_h2d_second = second_transfer_stream(self.device)
         self.pool = tg.tg_pool_create(self.slab.data_ptr(), capacity, align)
         self.base = self.slab.data_ptr()
+        self.last_timing: dict = {}            # tg_timing of the most recent load
+
+    def set_tuning(self, **kw) -> None:
+        tg.tg_pool_set_tuning(self.pool, **kw)
+
+    def set_profiling(self, on: bool) -> None:
+        tg.tg_pool_set_profiling(self.pool, on)
 
     def close(self) -> None:
         if self.pool is not None:
@@ -243,25 +257,82 @@ class ReusePool:
                                           str(self.device))
         return RegisteredModel(model_id, host, offs, sizes, fps)
 
+    @staticmethod
+    def _plan_flags(confirm=False, evict=False, merge=False, alias=False, pack_text=False) -> int:
+        return ((tg.TG_PLAN_CONFIRM if confirm else 0) | (tg.TG_PLAN_EVICT if evict else 0)
+                | (tg.TG_PLAN_MERGE if merge else 0) | (tg.TG_PLAN_ALIAS if alias else 0)
+                | (tg.TG_PLAN_PACK_TEXT if pack_text else 0))
+
+    def _plan_info(self, plan, details: bool) -> dict:
+        info = tg.tg_plan_info(plan)
+        if details:
+            rows, _reused, _transfer = tg.tg_plan_ops(plan)
+            info.update({"ops": rows, "moves": tg.tg_plan_moves(plan),
+                         "evictions": tg.tg_plan_evictions(plan)})
+        return info
+
+    def _stream_args(self) -> dict:
+        return dict(stream_gather=self.stream_gather, stream_h2d=self.stream_h2d,
+                    stream_h2d_second=self.stream_h2d_second,
+                    use_second_h2d_stream=self.stream_h2d_second is not None)
+
     def load(self, model: RegisteredModel, confirm: bool = False, verify: bool = False,
              evict: bool = False, merge: bool = False, alias: bool = False,
              pack_text: bool = False, details: bool = True) -> Tuple[List[int], dict]:
         """tg_plan + tg_assemble.  Returns device addresses and what the plan held
-        (with details=False only its totals: no per-tensor rows are fetched)."""
-        flags = ((tg.TG_PLAN_CONFIRM if confirm else 0) | (tg.TG_PLAN_EVICT if evict else 0)
-                 | (tg.TG_PLAN_MERGE if merge else 0) | (tg.TG_PLAN_ALIAS if alias else 0)
-                 | (tg.TG_PLAN_PACK_TEXT if pack_text else 0))
+        (with details=False only its totals: no per-tensor rows are fetched);
+        info["timing"] is the plan's tg_timing."""
+        flags = self._plan_flags(confirm, evict, merge, alias, pack_text)
         plan = tg.tg_plan(self.pool, model.desc, flags, self.stream_gather)
         try:
-            info = tg.tg_plan_info(plan)
-            if details:
-                rows, _reused, _transfer = tg.tg_plan_ops(plan)
-                info.update({"ops": rows, "moves": tg.tg_plan_moves(plan),
-                             "evictions": tg.tg_plan_evictions(plan)})
+            info = self._plan_info(plan, details)
             ptrs = tg.tg_assemble_ex(self.pool, plan, model.desc.n,
-                                     tg.TG_ASSEMBLE_VERIFY if verify else 0,
-                                     self.stream_gather, self.stream_h2d, self.stream_h2d_second,
-                                     use_second_h2d_stream=self.stream_h2d_second is not None)
+                                     tg.TG_ASSEMBLE_VERIFY if verify else 0, **self._stream_args())
+            info["timing"] = self.last_timing = tg.tg_plan_timing(plan)
+        finally:
+            tg.tg_plan_free(plan)
+        return ptrs, info
+
+    def load_streamed(self, model: RegisteredModel, segments, verify: bool = False, evict: bool = False,
+                      merge: bool = False, alias: bool = False, pack_text: bool = False,
+                      details: bool = True) -> Tuple[List[int], dict]:
+        """A load whose missing tensors pass through a Model Cache smaller than
+        the model: tg_plan (no host image needed), tg_assemble_begin, then one
+        tg_assemble_feed per segment, then tg_assemble_wait.
+
+        ``segments(missing)`` is a generator: given the indices of the tensors
+        the plan transfers, it yields (pinned address, length, [(tensor index,
+        offset in the segment)]) each time its buffer holds the next piece; it is
+        resumed only after the device has read the previous piece.
+        info["library_s"] is the time spent inside the library's calls and
+        waiting for the device; the rest of the wall time is the generator
+        refilling its buffer."""
+        flags = self._plan_flags(False, evict, merge, alias, pack_text)
+        t0 = time.perf_counter()
+        plan = tg.tg_plan(self.pool, model.desc, flags, self.stream_gather)
+        lib_s = time.perf_counter() - t0
+        try:
+            info = self._plan_info(plan, True)
+            missing = [k for k, op in enumerate(info["ops"]) if op[0] == tg.TG_OP_H2D]
+            if not details:
+                for key in ("ops", "moves", "evictions"):
+                    info.pop(key)
+            t0 = time.perf_counter()
+            tg.tg_assemble_begin(self.pool, plan, tg.TG_ASSEMBLE_VERIFY if verify else 0, **self._stream_args())
+            lib_s += time.perf_counter() - t0
+            n_feeds = 0
+            for ptr, nbytes, rows in segments(missing):
+                t0 = time.perf_counter()
+                ticket = tg.tg_assemble_feed(self.pool, plan, ptr, nbytes, rows)
+                tg.tg_assemble_feed_wait(self.pool, plan, ticket)
+                lib_s += time.perf_counter() - t0
+                n_feeds += 1
+            t0 = time.perf_counter()
+            ptrs = tg.tg_assemble_wait(self.pool, plan, model.desc.n)
+            lib_s += time.perf_counter() - t0
+            info["timing"] = self.last_timing = tg.tg_plan_timing(plan)
+            info["library_s"] = lib_s
+            info["feeds"] = n_feeds
         finally:
             tg.tg_plan_free(plan)
         return ptrs, info

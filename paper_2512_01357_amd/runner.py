@@ -19,8 +19,13 @@ class WorkloadRunner:
     """
 
     def __init__(self, w: synth.Workload, device: str = "cuda:0", gen_device: Optional[str] = None,
-                 log=None, arena_budget: int = 56 << 30):
+                 log=None, arena_budget: int = 56 << 30, segment_bytes: int = 48 * 10**9):
         self.w = w
+        self.arena_budget = arena_budget
+        self.segment_bytes = segment_bytes
+        self.seg_arena: Optional[HostArena] = None
+        self.on_segment = None                  # hook(name, rows, arena): called whenever a segment has been filled
+        self._fp_by_content: Dict[tuple, int] = {}
         self.device = device
         self.gen_device = gen_device or device
         self.log = log or (lambda *_: None)
@@ -52,6 +57,73 @@ class WorkloadRunner:
     def host_numpy(self, name: str):
         return self.models[name].host_tensor.numpy()
 
+    # ------------------------------------------------------------------ models too large to pin
+    def is_streamed(self, name: str) -> bool:
+        """True for a model that does not fit the Model Cache: it is registered
+        without a host image and loaded segment by segment."""
+        return self.w.streamed and synth.host_bytes(self.w.models[name], self.w.align) > self.arena_budget
+
+    def _segment_arena(self, need: int) -> HostArena:
+        want = min(self.segment_bytes, need)
+        if self.seg_arena is None or self.seg_arena.nbytes < want:
+            if self.seg_arena is not None:
+                self.seg_arena.free()
+            t0 = time.time()
+            self.seg_arena = HostArena(want)
+            self.log("model cache segment: %.1f GB pinned in %.1f s" % (want / 1e9, time.time() - t0))
+        return self.seg_arena
+
+    def segments(self, name: str):
+        """A generator factory for ReusePool.load_streamed: given tensor indices
+        of model `name`, fills the pinned segment with as many of them as fit,
+        in the given order, and yields (address, length, [(index, offset)])."""
+        spec = self.w.models[name]
+        a = self.w.align
+
+        def gen(ks):
+            if not ks:
+                return
+            slot = [(spec.tensors[k].nbytes + a - 1) // a * a for k in ks]
+            arena = self._segment_arena(max(sum(slot), a))
+            if max(slot) > arena.nbytes:
+                raise RuntimeError("a tensor is larger than the Model Cache segment")
+            i = 0
+            while i < len(ks):
+                rows, at = [], 0
+                while i < len(ks) and at + slot[i] <= arena.nbytes:
+                    t = spec.tensors[ks[i]]
+                    arena.tensor[at:at + t.nbytes].copy_(synth.tensor_bytes(t, self.gen_device))
+                    rows.append((ks[i], at))
+                    at += slot[i]
+                    i += 1
+                if self.on_segment is not None:
+                    self.on_segment(name, rows, arena)
+                yield arena.ptr, at, rows
+        return gen
+
+    def _register_streamed(self, name: str) -> RegisteredModel:
+        """Fingerprints of a model that passes through the segment piece by
+        piece: each piece is fingerprinted where it lies, in pinned host memory,
+        through its device mapping (tensors whose content was fingerprinted
+        before -- a sibling's -- are not read again)."""
+        from . import tangram as tg
+        spec = self.w.models[name]
+        t0 = time.time()
+        fps = [self._fp_by_content.get(synth.content_key(t)) for t in spec.tensors]
+        todo = [k for k, f in enumerate(fps) if f is None]
+        for ptr, _n, rows in self.segments(name)(todo):
+            dev = tg.tg_host_device_ptr(ptr)
+            got = tg.tg_fingerprint([(dev + off, spec.tensors[k].nbytes) for k, off in rows], self.pool.stream_gather)
+            for (k, _off), f in zip(rows, got):
+                fps[k] = f
+                self._fp_by_content[synth.content_key(spec.tensors[k])] = f
+        sizes = [t.nbytes for t in spec.tensors]
+        reg = RegisteredModel(spec.model_id, None, synth.layout(spec, self.w.align), sizes, fps)
+        self.models[name] = reg
+        self.log("registered %s: %d tensors, %.3f GB (%d fingerprinted over the host link) in %.1f s"
+                 % (name, len(sizes), sum(sizes) / 1e9, len(todo), time.time() - t0))
+        return reg
+
     def _build_main(self) -> None:
         t0 = time.time()
         specs = [self.w.models[n] for n in self._main_names]
@@ -78,6 +150,8 @@ class WorkloadRunner:
         if name in self._main_names:
             self._build_main()
             return self.models[name]
+        if self.is_streamed(name):
+            return self._register_streamed(name)
         spec = self.w.models[name]
         t0 = time.time()
         host = HostArena(synth.host_bytes(spec, self.w.align))
@@ -93,6 +167,8 @@ class WorkloadRunner:
         """Forget a model's private host image (its tensors stay in the pool)."""
         if name in self._main_names:
             return
+        if name in self.models and self.models[name].host is None:
+            return                               # rows only: nothing to free
         reg = self.models.pop(name, None)
         if reg is not None and isinstance(reg.host, HostArena):
             reg.host_tensor = None
@@ -101,8 +177,7 @@ class WorkloadRunner:
     def run_setup(self) -> None:
         for act in self.w.setup:
             if act[0] == "load":
-                reg = self.materialise(act[1])
-                self.pool.load(reg)
+                self.load(act[1], details=False)
                 self.log("setup: loaded %s" % act[1])
                 self.drop_host(act[1])
             else:
@@ -116,6 +191,10 @@ class WorkloadRunner:
         reg = self.materialise(name)
         if not flags and name in self.w.loads:
             flags = dict(self.w.load_flags)
+        if reg.host is None:
+            if confirm:
+                raise ValueError("confirmation needs the model's whole host image")
+            return self.pool.load_streamed(reg, self.segments(name), verify=verify, details=details, **flags)
         return self.pool.load(reg, confirm=confirm, verify=verify, details=details, **flags)
 
     def reset_pool(self) -> None:
@@ -139,3 +218,6 @@ class WorkloadRunner:
         if self.arena is not None:
             self.arena.free()
             self.arena = None
+        if self.seg_arena is not None:
+            self.seg_arena.free()
+            self.seg_arena = None

@@ -68,8 +68,8 @@ class Workload:
     setup: List[tuple]
     loads: List[str]
     designated_shared: Dict[str, int] = field(default_factory=dict)
-    # True when the measured model is cut into parts that pass through the
-    # Model Cache one after the other (all parts together are one load)
+    # True when models larger than the pinned Model Cache are registered without
+    # a host image and reach the pool segment by segment
     streamed: bool = False
     # plan flags for the measured loads: any of "evict", "merge", "alias"
     load_flags: Dict[str, bool] = field(default_factory=dict)
@@ -284,84 +284,65 @@ def workload_neox20b_tight(pool_gb: float = 72.0) -> Workload:
     return w
 
 
-def split_model(spec: ModelSpec, max_bytes: int, id_base: int, interleave: bool = False) -> List[ModelSpec]:
-    """Cuts a model into parts of at most max_bytes (a Model Cache smaller than
-    the model streams it part by part).  Part p is a model of its own, named
-    "<name>.p<p>", with id id_base + p.
-
-    By default a part is a run of consecutive tensors.  With `interleave`,
-    transformer layer L goes to part L mod P and the other tensors to the
-    lightest part: siblings of a model family tend to differ in a run of
-    neighbouring layers, and dealing the layers out gives every part its share
-    of the tensors that have to be transferred, so each part's gather hides
-    under its own transfer instead of all the transfers meeting in one part."""
-    if not interleave:
-        parts: List[List[TensorSpec]] = [[]]
-        size = 0
-        for t in spec.tensors:
-            if parts[-1] and size + t.nbytes > max_bytes:
-                parts.append([])
-                size = 0
-            parts[-1].append(t)
-            size += t.nbytes
-    else:
-        n = max(1, -(-spec.nbytes // max_bytes))
-        while True:
-            parts = [[] for _ in range(n)]
-            sizes = [0] * n
-            for t in spec.tensors:
-                lay = layer_of(t.name)
-                if lay is not None:
-                    parts[lay % n].append(t)
-                    sizes[lay % n] += t.nbytes
-            for t in spec.tensors:
-                if layer_of(t.name) is None:
-                    p = sizes.index(min(sizes))
-                    parts[p].append(t)
-                    sizes[p] += t.nbytes
-            if max(sizes) <= max_bytes or n >= len(spec.tensors):
-                break
-            n += 1
-        parts = [ts for ts in parts if ts]
-    return [ModelSpec("%s.p%d" % (spec.name, p), id_base + p, ts) for p, ts in enumerate(parts)]
-
-
-def workload_llama70b(reuse: float, pool_bytes: int, part_bytes: int = 48 * 10**9,
-                      load_part_bytes: int = 50 * 10**9) -> Workload:
-    """Config 5: 70B Llama-3-shaped model; a resident sibling holds the
-    designated share of its tensors (0, 50 or 90 %).  Both go through the
-    Model Cache in parts; the measured model's layers are dealt out over its
-    parts (see split_model)."""
-    shapes = llama_tensors(8192, 80, 28672, 128256, 1024)
-
+def _llama70b_keep(reuse: float):
+    """Which tensors a 70B model shares with its resident sibling at a designated reuse level."""
     if reuse <= 0.0:
-        def keep(k, nm):
-            return False
-    elif reuse <= 0.5:
-        def keep(k, nm):
+        return lambda k, nm: False
+    if reuse <= 0.5:
+        def keep50(k, nm):
             lay = layer_of(nm)
             return nm == "embed" or (lay is not None and lay < 40)
-    else:
-        def keep(k, nm):
-            lay = layer_of(nm)
-            return nm in ("embed", "lm_head", "final_norm") or (lay is not None and lay < 72)
+        return keep50
+
+    def keep90(k, nm):
+        lay = layer_of(nm)
+        return nm in ("embed", "lm_head", "final_norm") or (lay is not None and lay < 72)
+    return keep90
+
+
+LLAMA70B_SHAPES = dict(h=8192, layers=80, ffn=28672, vocab=128256, kv_dim=1024)
+
+
+def workload_llama70b(reuse: float, pool_bytes: int) -> Workload:
+    """Config 5: 70B Llama-3-shaped model (723 tensors, 141 GB) loaded as one
+    model; a resident sibling holds the designated share of its tensors (0, 50
+    or 90 %).  Neither fits pinned host memory at once, so both are registered
+    without a host image and pass through the Model Cache segment by segment
+    (`streamed`)."""
+    shapes = llama_tensors(**LLAMA70B_SHAPES)
+    keep = _llama70b_keep(reuse)
     models: Dict[str, ModelSpec] = {}
     setup: List[tuple] = []
     sib = make_model("sib", 1, shapes, 5, 0, gains_one=True, subset=keep)
     if sib.tensors:
-        # the sibling reaches the pool in parts: the box cannot pin 127 GB at once
-        for part in split_model(sib, part_bytes, 100):
-            models[part.name] = part
-            setup += [("load", part.name), ("release", part.name, False)]
-    m = make_model("M70", 2, shapes, 5, 1, gains_one=True,
-                   share_from=sib if sib.tensors else None, shared=keep)
-    loads = []
-    for part in split_model(m, load_part_bytes, 200, interleave=True):
-        models[part.name] = part
-        loads.append(part.name)
+        models["sib"] = sib
+        setup += [("load", "sib"), ("release", "sib", False)]
+    models["M70"] = make_model("M70", 2, shapes, 5, 1, gains_one=True,
+                               share_from=sib if sib.tensors else None, shared=keep)
     n_shared = sum(1 for k, (nm, _, _) in enumerate(shapes) if keep(k, nm))
     w = Workload("llama3-70b-reuse%02d" % int(round(reuse * 100)),
-                 pool_bytes // 256 * 256, 256, models, setup, loads, {"M70": n_shared})
+                 pool_bytes // 256 * 256, 256, models, setup, ["M70"], {"M70": n_shared})
+    w.streamed = True
+    return w
+
+
+def workload_llama70b_sweep(pool_bytes: int, levels=(0.9, 0.5, 0.0)) -> Workload:
+    """Config 5's three reuse levels against one pool: the resident sibling is
+    the 90 % one (embeddings, lm_head, final norm, layers 0-71: 127 GB); the
+    model measured at level r shares with it exactly the tensors designated for
+    r and brings its own bytes for the rest.  Loads are named "M70-<percent>"."""
+    shapes = llama_tensors(**LLAMA70B_SHAPES)
+    sib = make_model("sib", 1, shapes, 5, 0, gains_one=True, subset=_llama70b_keep(0.9))
+    models: Dict[str, ModelSpec] = {"sib": sib}
+    loads, shared = [], {}
+    for i, r in enumerate(levels):
+        keep = _llama70b_keep(r)
+        name = "M70-%d" % int(round(r * 100))
+        models[name] = make_model(name, 2 + i, shapes, 5, 1, gains_one=True, share_from=sib, shared=keep)
+        loads.append(name)
+        shared[name] = sum(1 for k, (nm, _, _) in enumerate(shapes) if keep(k, nm))
+    w = Workload("llama3-70b-sweep", pool_bytes // 256 * 256, 256, models,
+                 [("load", "sib"), ("release", "sib", False)], loads, shared)
     w.streamed = True
     return w
 

@@ -92,18 +92,21 @@ class tg_plan_summary(ctypes.Structure):
 
 class tg_timing(ctypes.Structure):
     _fields_ = ([(n, ctypes.c_float) for n in (
-        "fingerprint_ms", "compare_ms", "gather_ms", "h2d_ms", "verify_ms", "plan_host_ms")]
-        + [(n, ctypes.c_uint64) for n in (
-            "fingerprint_bytes", "compare_bytes", "gather_bytes", "h2d_bytes", "verify_bytes")]
-        + [("h2d_copies", ctypes.c_uint32), ("move_launches", ctypes.c_uint32),
-           ("move_ms", ctypes.c_float), ("verify_launches", ctypes.c_uint32),
-           ("move_bytes", ctypes.c_uint64), ("move_traffic_bytes", ctypes.c_uint64)])
+        "compare_ms", "gather_ms", "h2d_ms", "verify_ms", "plan_host_ms", "move_ms")]
+        + [(n, ctypes.c_uint64) for n in ("compare_bytes", "gather_bytes", "h2d_bytes", "verify_bytes")]
+        + [(n, ctypes.c_uint32) for n in ("h2d_copies", "move_launches", "verify_launches", "feeds")]
+        + [("move_bytes", ctypes.c_uint64), ("move_traffic_bytes", ctypes.c_uint64)])
 
 
 class tg_tuning(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in (
         "fingerprint_unroll", "fingerprint_wgs_per_cu", "gather_unroll", "gather_wgs_per_cu",
-        "compare_unroll", "compare_wgs_per_cu")] + [("h2d_kernel_max_bytes", ctypes.c_uint64)]
+        "compare_unroll", "compare_wgs_per_cu")] + [("h2d_kernel_max_bytes", ctypes.c_uint64),
+                                                     ("h2d_group_bytes", ctypes.c_uint64)]
+
+
+class tg_feed_row(ctypes.Structure):
+    _fields_ = [("tensor", ctypes.c_uint32), ("reserved", ctypes.c_uint32), ("seg_off", ctypes.c_uint64)]
 
 
 class TgError(RuntimeError):
@@ -115,10 +118,14 @@ class TgError(RuntimeError):
 _lib = None
 
 EXPORTS = [
-    "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_pool_regions", "tg_pool_entries", "tg_fingerprint", "tg_fingerprint_noalloc", "tg_compare",
-    "tg_plan", "tg_plan_ops", "tg_plan_info", "tg_plan_moves", "tg_plan_evictions", "tg_plan_free",
-    "tg_assemble", "tg_assemble_ex", "tg_commit", "tg_abandon", "tg_release", "tg_set_model_cost", "tg_reuse_size", "tg_set_tuning", "tg_get_tuning", "tg_set_profiling", "tg_last_timing",
-    "tg_host_alloc", "tg_host_free", "tg_shutdown", "tg_strerror",
+    "tg_pool_create", "tg_pool_destroy", "tg_pool_stats", "tg_pool_regions", "tg_pool_entries",
+    "tg_default_tuning", "tg_pool_set_tuning", "tg_pool_get_tuning", "tg_pool_set_profiling",
+    "tg_measure_mix_rate", "tg_fingerprint", "tg_fingerprint_ex", "tg_fingerprint_noalloc", "tg_compare", "tg_compare_ex",
+    "tg_plan", "tg_plan_ops", "tg_plan_info", "tg_plan_moves", "tg_plan_evictions", "tg_plan_timing", "tg_plan_free",
+    "tg_assemble", "tg_assemble_ex", "tg_assemble_async", "tg_assemble_begin", "tg_assemble_feed",
+    "tg_assemble_feed_wait", "tg_assemble_wait", "tg_commit", "tg_abandon", "tg_release",
+    "tg_set_model_cost", "tg_reuse_size", "tg_host_alloc", "tg_host_free", "tg_host_device_ptr", "tg_shutdown",
+    "tg_strerror",
 ]
 
 
@@ -139,7 +146,19 @@ def lib() -> ctypes.CDLL:
             "tg_pool_stats": ([vp, P(tg_stats)], i32),
             "tg_pool_regions": ([vp, P(tg_region), u32, P(u32)], i32),
             "tg_pool_entries": ([vp, P(tg_entry), u32, P(u32)], i32),
+            "tg_default_tuning": ([P(tg_tuning)], i32),
+            "tg_pool_set_tuning": ([vp, P(tg_tuning)], i32),
+            "tg_pool_get_tuning": ([vp, P(tg_tuning)], i32),
+            "tg_pool_set_profiling": ([vp, ctypes.c_int], i32),
             "tg_fingerprint": ([P(tg_span), u32, P(u64), vp], i32),
+            "tg_fingerprint_ex": ([P(tg_span), u32, P(u64), vp, P(tg_tuning), P(ctypes.c_float)], i32),
+            "tg_compare_ex": ([P(tg_pair), u32, P(u32), vp, P(tg_tuning), P(ctypes.c_float)], i32),
+            "tg_plan_timing": ([vp, P(tg_timing)], i32),
+            "tg_assemble_async": ([vp, vp, P(tg_assemble_args)], i32),
+            "tg_assemble_begin": ([vp, vp, P(tg_assemble_args)], i32),
+            "tg_assemble_feed": ([vp, vp, vp, u64, P(tg_feed_row), u32, P(u32)], i32),
+            "tg_assemble_feed_wait": ([vp, vp, u32], i32),
+            "tg_assemble_wait": ([vp, vp, P(vp)], i32),
             "tg_fingerprint_noalloc": ([P(tg_span), u32, P(u64), vp], i32),
             "tg_compare": ([P(tg_pair), u32, P(u32), vp], i32),
             "tg_plan": ([vp, P(tg_model_desc), u32, vp, P(vp)], i32),
@@ -155,12 +174,10 @@ def lib() -> ctypes.CDLL:
             "tg_abandon": ([vp, vp], i32),
             "tg_release": ([vp, u64, u32], i32),
             "tg_reuse_size": ([vp, P(tg_model_desc), ctypes.c_double, P(u64), P(ctypes.c_double)], i32),
-            "tg_set_tuning": ([P(tg_tuning)], i32),
-            "tg_get_tuning": ([P(tg_tuning)], i32),
-            "tg_set_profiling": ([ctypes.c_int], None),
-            "tg_last_timing": ([P(tg_timing)], i32),
             "tg_host_alloc": ([u64, P(vp)], i32),
             "tg_host_free": ([vp], i32),
+            "tg_host_device_ptr": ([vp, P(vp)], i32),
+            "tg_measure_mix_rate": ([u32, vp, P(ctypes.c_double)], i32),
             "tg_shutdown": ([], None),
             "tg_strerror": ([i32], ctypes.c_char_p),
         }
@@ -228,16 +245,42 @@ def tg_pool_entries(pool) -> List[Tuple[int, int, int, int, int]]:
 
 
 # ---------------------------------------------------------------- device ops
-def tg_fingerprint(spans: Sequence[Tuple[int, int]], stream=None) -> List[int]:
-    """spans: (device address, nbytes) rows.  Returns their fingerprints."""
+def _span_array(spans):
     n = len(spans)
     arr = (tg_span * max(n, 1))()
     for i, (ptr, nbytes) in enumerate(spans):
         arr[i].ptr = ptr
         arr[i].nbytes = nbytes
+    return arr, n
+
+
+def _tuning(tuning: Optional[dict]):
+    """A tg_tuning made of the defaults overridden by `tuning`, or None."""
+    if tuning is None:
+        return None
+    cur = tg_default_tuning()
+    cur.update(tuning)
+    return tg_tuning(**cur)
+
+
+def tg_fingerprint(spans: Sequence[Tuple[int, int]], stream=None) -> List[int]:
+    """spans: (device address, nbytes) rows.  Returns their fingerprints."""
+    arr, n = _span_array(spans)
     out = (ctypes.c_uint64 * max(n, 1))()
     _check(lib().tg_fingerprint(arr, n, out, _stream(stream)), "tg_fingerprint")
     return [int(out[i]) for i in range(n)]
+
+
+def tg_fingerprint_ex(spans: Sequence[Tuple[int, int]], stream=None, tuning: Optional[dict] = None,
+                      timed: bool = False) -> Tuple[List[int], Optional[float]]:
+    """(fingerprints, kernel milliseconds or None); tuning: fields of tg_tuning to override."""
+    arr, n = _span_array(spans)
+    out = (ctypes.c_uint64 * max(n, 1))()
+    t = _tuning(tuning)
+    ms = ctypes.c_float()
+    _check(lib().tg_fingerprint_ex(arr, n, out, _stream(stream), ctypes.byref(t) if t is not None else None,
+                                   ctypes.byref(ms) if timed else None), "tg_fingerprint_ex")
+    return [int(out[i]) for i in range(n)], (float(ms.value) if timed else None)
 
 
 TG_NOALLOC_MAX_SPANS = 4096
@@ -246,27 +289,39 @@ TG_NOALLOC_MAX_SPANS = 4096
 def tg_fingerprint_noalloc(spans: Sequence[Tuple[int, int]], stream=None) -> List[int]:
     """tg_fingerprint through the entry point that allocates nothing (at most
     TG_NOALLOC_MAX_SPANS spans)."""
-    n = len(spans)
-    arr = (tg_span * max(n, 1))()
-    for i, (ptr, nbytes) in enumerate(spans):
-        arr[i].ptr = ptr
-        arr[i].nbytes = nbytes
+    arr, n = _span_array(spans)
     out = (ctypes.c_uint64 * max(n, 1))()
     _check(lib().tg_fingerprint_noalloc(arr, n, out, _stream(stream)), "tg_fingerprint_noalloc")
     return [int(out[i]) for i in range(n)]
 
 
-def tg_compare(pairs: Sequence[Tuple[int, int, int]], stream=None) -> List[int]:
-    """pairs: (address a, address b, nbytes) rows.  1 where the bytes differ."""
+def _pair_array(pairs):
     n = len(pairs)
     arr = (tg_pair * max(n, 1))()
     for i, (a, b, nbytes) in enumerate(pairs):
         arr[i].a = a
         arr[i].b = b
         arr[i].nbytes = nbytes
+    return arr, n
+
+
+def tg_compare(pairs: Sequence[Tuple[int, int, int]], stream=None) -> List[int]:
+    """pairs: (address a, address b, nbytes) rows.  1 where the bytes differ."""
+    arr, n = _pair_array(pairs)
     out = (ctypes.c_uint32 * max(n, 1))()
     _check(lib().tg_compare(arr, n, out, _stream(stream)), "tg_compare")
     return [int(out[i]) for i in range(n)]
+
+
+def tg_compare_ex(pairs: Sequence[Tuple[int, int, int]], stream=None, tuning: Optional[dict] = None,
+                  timed: bool = False) -> Tuple[List[int], Optional[float]]:
+    arr, n = _pair_array(pairs)
+    out = (ctypes.c_uint32 * max(n, 1))()
+    t = _tuning(tuning)
+    ms = ctypes.c_float()
+    _check(lib().tg_compare_ex(arr, n, out, _stream(stream), ctypes.byref(t) if t is not None else None,
+                               ctypes.byref(ms) if timed else None), "tg_compare_ex")
+    return [int(out[i]) for i in range(n)], (float(ms.value) if timed else None)
 
 
 # --------------------------------------------------------------------- model
@@ -355,6 +410,46 @@ def tg_assemble_ex(pool, plan, n_tensors: int, flags: int = 0, stream_gather=Non
     return [int(out[k] or 0) for k in range(n_tensors)]
 
 
+def _assemble_args(flags, stream_gather, stream_h2d, stream_h2d_second, use_second_h2d_stream):
+    return tg_assemble_args(flags, 1 if use_second_h2d_stream else 0, _stream(stream_gather),
+                            _stream(stream_h2d), _stream(stream_h2d_second))
+
+
+def tg_assemble_async(pool, plan, flags: int = 0, stream_gather=None, stream_h2d=None,
+                      stream_h2d_second=None, use_second_h2d_stream: bool = False) -> None:
+    args = _assemble_args(flags, stream_gather, stream_h2d, stream_h2d_second, use_second_h2d_stream)
+    _check(lib().tg_assemble_async(pool, plan, ctypes.byref(args)), "tg_assemble_async")
+
+
+def tg_assemble_begin(pool, plan, flags: int = 0, stream_gather=None, stream_h2d=None,
+                      stream_h2d_second=None, use_second_h2d_stream: bool = False) -> None:
+    args = _assemble_args(flags, stream_gather, stream_h2d, stream_h2d_second, use_second_h2d_stream)
+    _check(lib().tg_assemble_begin(pool, plan, ctypes.byref(args)), "tg_assemble_begin")
+
+
+def tg_assemble_feed(pool, plan, seg_base: int, seg_bytes: int, rows: Sequence[Tuple[int, int]]) -> int:
+    """rows: (tensor index, offset inside the segment).  Returns the feed's ticket."""
+    n = len(rows)
+    arr = (tg_feed_row * max(n, 1))()
+    for i, (k, off) in enumerate(rows):
+        arr[i].tensor = k
+        arr[i].seg_off = off
+    ticket = ctypes.c_uint32()
+    _check(lib().tg_assemble_feed(pool, plan, ctypes.c_void_p(seg_base), seg_bytes, arr, n,
+                                  ctypes.byref(ticket)), "tg_assemble_feed")
+    return int(ticket.value)
+
+
+def tg_assemble_feed_wait(pool, plan, ticket: int) -> None:
+    _check(lib().tg_assemble_feed_wait(pool, plan, ticket), "tg_assemble_feed_wait")
+
+
+def tg_assemble_wait(pool, plan, n_tensors: int) -> List[int]:
+    out = (ctypes.c_void_p * max(n_tensors, 1))()
+    _check(lib().tg_assemble_wait(pool, plan, out), "tg_assemble_wait")
+    return [int(out[k] or 0) for k in range(n_tensors)]
+
+
 def tg_commit(pool, plan, n_tensors: int) -> List[int]:
     out = (ctypes.c_void_p * max(n_tensors, 1))()
     _check(lib().tg_commit(pool, plan, out), "tg_commit")
@@ -383,27 +478,34 @@ def tg_reuse_size(pool, model: ModelDesc, link_bytes_per_s: Optional[float] = No
 
 
 # ------------------------------------------------------------ tuning, timing
-def tg_get_tuning() -> dict:
+def tg_default_tuning() -> dict:
     t = tg_tuning()
-    _check(lib().tg_get_tuning(ctypes.byref(t)), "tg_get_tuning")
+    _check(lib().tg_default_tuning(ctypes.byref(t)), "tg_default_tuning")
     return {n: int(getattr(t, n)) for n, _ in tg_tuning._fields_}
 
 
-def tg_set_tuning(**kw) -> None:
-    cur = tg_get_tuning()
+def tg_pool_get_tuning(pool) -> dict:
+    t = tg_tuning()
+    _check(lib().tg_pool_get_tuning(pool, ctypes.byref(t)), "tg_pool_get_tuning")
+    return {n: int(getattr(t, n)) for n, _ in tg_tuning._fields_}
+
+
+def tg_pool_set_tuning(pool, **kw) -> None:
+    """Overrides the named fields of the pool's tg_tuning."""
+    cur = tg_pool_get_tuning(pool)
     cur.update(kw)
     t = tg_tuning(**cur)
-    _check(lib().tg_set_tuning(ctypes.byref(t)), "tg_set_tuning")
+    _check(lib().tg_pool_set_tuning(pool, ctypes.byref(t)), "tg_pool_set_tuning")
 
 
-def tg_set_profiling(on: bool) -> None:
-    lib().tg_set_profiling(1 if on else 0)
+def tg_pool_set_profiling(pool, on: bool) -> None:
+    _check(lib().tg_pool_set_profiling(pool, 1 if on else 0), "tg_pool_set_profiling")
 
 
-def tg_last_timing() -> dict:
+def tg_plan_timing(plan) -> dict:
     t = tg_timing()
-    _check(lib().tg_last_timing(ctypes.byref(t)), "tg_last_timing")
-    return {n: getattr(t, n) for n, _ in tg_timing._fields_ if n != "reserved"}
+    _check(lib().tg_plan_timing(plan, ctypes.byref(t)), "tg_plan_timing")
+    return {n: getattr(t, n) for n, _ in tg_timing._fields_}
 
 
 def tg_host_alloc(nbytes: int) -> int:
@@ -415,6 +517,20 @@ def tg_host_alloc(nbytes: int) -> int:
 
 def tg_host_free(ptr: int) -> None:
     _check(lib().tg_host_free(ctypes.c_void_p(ptr)), "tg_host_free")
+
+
+def tg_measure_mix_rate(iters: int = 4096, stream=None) -> float:
+    """Words per second of the fingerprint's arithmetic without its loads."""
+    out = ctypes.c_double()
+    _check(lib().tg_measure_mix_rate(iters, _stream(stream), ctypes.byref(out)), "tg_measure_mix_rate")
+    return float(out.value)
+
+
+def tg_host_device_ptr(ptr: int) -> int:
+    """The device-side address of a piece of pinned host memory."""
+    out = ctypes.c_void_p()
+    _check(lib().tg_host_device_ptr(ctypes.c_void_p(ptr), ctypes.byref(out)), "tg_host_device_ptr")
+    return int(out.value)
 
 
 def tg_shutdown() -> None:

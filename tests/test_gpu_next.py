@@ -107,7 +107,6 @@ def test_hand_derived_merge_plan_moves_real_bytes():
                    (1, True), (4, False)], U)
     plan, dsts = b.load(9, [rbytes(rnd, 6 * U), rbytes(rnd, 5 * U - 7)], merge=True)
     assert [(o // U, n // U) for _e, o, n in plan.moves] == [(4, 0), (20, 16), (25, 17)]
-    t = tg.tg_last_timing()
     b.close()
 
 
@@ -156,15 +155,15 @@ def test_failed_verification_after_moves_and_evictions_leaves_a_consistent_pool(
 
 def test_large_moves_straight_and_staged():
     say("merge with large shifts (straight copies) and small shifts over long tensors (staged)")
-    tg.tg_set_profiling(True)
     rnd = random.Random(2)
     # F64 A200 F64 B40 F100 (MiB): a 210 MiB tensor fits nowhere; everything is compacted.
     # A shifts by 64 MiB (straight, in pieces of at most 64 MiB), B by 128 MiB.
     b = Both(468 * MIB)
+    b.pool.set_profiling(True)
     carve(b, rnd, [(64, False), (200, True), (64, False), (40, True), (100, False)], MIB)
     plan, _ = b.load(9, [rbytes(rnd, 210 * MIB + 40)], merge=True)
     assert [(o // MIB, n // MIB) for _e, o, n in plan.moves] == [(64, 0), (328, 200)]
-    t = tg.tg_last_timing()
+    t = b.pool.last_timing
     assert t["move_bytes"] == 240 * MIB and t["move_traffic_bytes"] == 2 * 240 * MIB
     # A goes in pieces of 64 + 64 + 64 + 8 MiB (a launch may not write at or above the first byte
     # it reads, 64 MiB ahead); B's 40 MiB land below that mark too and ride in the last launch
@@ -175,10 +174,9 @@ def test_large_moves_straight_and_staged():
     carve(b, rnd, [(1, False), (300, True), (100, False)], MIB)
     plan, _ = b.load(9, [rbytes(rnd, 101 * MIB - 3)], merge=True)
     assert [(o // MIB, n // MIB) for _e, o, n in plan.moves] == [(1, 0)]
-    t = tg.tg_last_timing()
+    t = b.pool.last_timing
     assert t["move_launches"] == 6 and t["move_traffic_bytes"] == 4 * 300 * MIB
     b.close()
-    tg.tg_set_profiling(False)
 
 
 def test_a_moved_tensor_that_no_longer_matches_its_row_is_dropped():

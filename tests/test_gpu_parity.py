@@ -56,22 +56,18 @@ LENGTHS = [0, 1, 7, 8, 9, 15, 16, 17, 31, 4095, 4096, 4097, 8192, 16384 - 16, 16
 @pytest.mark.parametrize("unroll", [2, 4, 8, 16])
 def test_fingerprint_matches_oracle_on_ragged_lengths(unroll):
     say("fingerprint ragged lengths unroll=%d" % unroll)
-    old = tg.tg_get_tuning()
-    tg.tg_set_tuning(fingerprint_unroll=unroll)
-    try:
-        rnd = random.Random(unroll)
-        datas = [random_bytes(rnd, n) for n in LENGTHS]
-        bufs = [dev_bytes(d) for d in datas]
-        torch.cuda.synchronize()
-        spans = [(b.data_ptr(), len(d)) for b, d in zip(bufs, datas)]
-        got = tg.tg_fingerprint(spans)
-        want = [oracle.fingerprint(d) for d in datas]
-        assert got == want
-        # one span at a time gives the same values
-        for sp, w in zip(spans[:8], want[:8]):
-            assert tg.tg_fingerprint([sp]) == [w]
-    finally:
-        tg.tg_set_tuning(**old)
+    tuning = {"fingerprint_unroll": unroll}
+    rnd = random.Random(unroll)
+    datas = [random_bytes(rnd, n) for n in LENGTHS]
+    bufs = [dev_bytes(d) for d in datas]
+    torch.cuda.synchronize()
+    spans = [(b.data_ptr(), len(d)) for b, d in zip(bufs, datas)]
+    got, ms = tg.tg_fingerprint_ex(spans, tuning=tuning, timed=True)
+    want = [oracle.fingerprint(d) for d in datas]
+    assert got == want and ms > 0.0
+    # one span at a time gives the same values
+    for sp, w in zip(spans[:8], want[:8]):
+        assert tg.tg_fingerprint_ex([sp], tuning=tuning)[0] == [w]
 
 
 def test_fingerprint_golden_recipes_and_empty_call():
@@ -98,13 +94,9 @@ def test_fingerprint_many_small_spans_and_small_grid():
         spans.append((buf.data_ptr() + at, n))
         want.append(oracle.fingerprint(blob[at:at + n]))
         at += (n + 15) // 16 * 16
-    old = tg.tg_get_tuning()
-    try:
-        for wgs in (1, 4, 16):
-            tg.tg_set_tuning(fingerprint_wgs_per_cu=wgs)
-            assert tg.tg_fingerprint(spans) == want
-    finally:
-        tg.tg_set_tuning(**old)
+    for wgs in (1, 4, 16):
+        assert tg.tg_fingerprint_ex(spans, tuning={"fingerprint_wgs_per_cu": wgs})[0] == want
+    assert tg.tg_fingerprint(spans) == want
 
 
 def test_fingerprint_rejects_bad_arguments():
@@ -201,9 +193,8 @@ def test_fingerprint_on_a_stream_and_single_bit_flip():
 @pytest.mark.parametrize("unroll", [2, 8, 16])
 def test_compare_matches_oracle(unroll):
     say("compare unroll=%d" % unroll)
-    old = tg.tg_get_tuning()
-    tg.tg_set_tuning(compare_unroll=unroll)
-    try:
+    tuning = {"compare_unroll": unroll}
+    if True:
         rnd = random.Random(7 + unroll)
         pairs, want, keep = [], [], []
         for n in LENGTHS[1:]:
@@ -217,12 +208,12 @@ def test_compare_matches_oracle(unroll):
                 pairs.append((ta.data_ptr(), tb.data_ptr(), n))
                 want.append(0 if oracle.bytes_equal(bytes(a), bytes(b)) else 1)
         torch.cuda.synchronize()
+        got, ms = tg.tg_compare_ex(pairs, tuning=tuning, timed=True)
+        assert got == want and ms > 0.0
         assert tg.tg_compare(pairs) == want
         assert tg.tg_compare([]) == []
         # zero-length pair is equal
         assert tg.tg_compare([(keep[0].data_ptr(), keep[1].data_ptr(), 0)]) == [0]
-    finally:
-        tg.tg_set_tuning(**old)
 
 
 def pinned(data: np.ndarray) -> torch.Tensor:
@@ -286,11 +277,11 @@ class Both:
 @pytest.mark.parametrize("gather_unroll", [2, 4, 8, 16])
 def test_load_small_models_ragged_sizes(gather_unroll):
     say("assemble ragged sizes gather_unroll=%d" % gather_unroll)
-    old = tg.tg_get_tuning()
-    tg.tg_set_tuning(gather_unroll=gather_unroll)
-    try:
+    if True:
         rnd = random.Random(31 + gather_unroll)
         b = Both(64 << 20)
+        b.pool.set_tuning(gather_unroll=gather_unroll)
+        assert tg.tg_pool_get_tuning(b.pool.pool)["gather_unroll"] == gather_unroll
         sizes = [1, 7, 16, 24, 255, 256, 257, 4096, 5000, TILE_U8 - 16, TILE_U8, TILE_U8 + 8,
                  3 * TILE_U8 + 4096 + 5, TILE_COPY // 4, TILE_COPY // 2 + 16, TILE_COPY - 8,
                  TILE_COPY, TILE_COPY + 24, 2 * TILE_COPY, (1 << 20) + 24, 3 * (1 << 20) + 1]
@@ -309,26 +300,21 @@ def test_load_small_models_ragged_sizes(gather_unroll):
         b.release(3)
         b.check_image()
         b.close()
-    finally:
-        tg.tg_set_tuning(**old)
 
 
 @pytest.mark.parametrize("limit", [0, 65536, 1 << 20])
 def test_small_missing_tensors_through_the_gather_kernel(limit):
     say("small H2D via kernel, up to %d bytes (0: every missing tensor by the copy engine)" % limit)
-    old = tg.tg_get_tuning()
-    tg.tg_set_tuning(h2d_kernel_max_bytes=limit)
-    try:
+    if True:
         rnd = random.Random(41)
         b = Both(32 << 20)
+        b.pool.set_tuning(h2d_kernel_max_bytes=limit)
         a = [random_bytes(rnd, n) for n in (16, 512, 4096, 65536, 65537, 1 << 20, 24, 8192)]
         b.load(1, a, verify=True)
         b.release(1)
         m2 = [a[0], random_bytes(rnd, 512), a[5], random_bytes(rnd, 100000), random_bytes(rnd, 7)]
         b.load(2, m2, verify=True)
         b.close()
-    finally:
-        tg.tg_set_tuning(**old)
 
 
 def test_confirm_demotes_a_constructed_collision():

@@ -62,8 +62,12 @@ def rows_of(plan):
 
 
 def both_plan(pool, store, model_id, tensors, host_bytes):
-    """Plan on both sides; returns (library plan handle or None, oracle plan or None)."""
-    desc = tg.ModelDesc(model_id, FAKE_HOST, host_bytes, tensors)
+    """Plan on both sides; returns (library plan handle or None, oracle plan or None).
+    host_bytes None: the model has no host image (only rows)."""
+    if host_bytes is None:
+        desc = tg.ModelDesc(model_id, 0, 0, tensors)
+    else:
+        desc = tg.ModelDesc(model_id, FAKE_HOST, host_bytes, tensors)
     try:
         oplan = store.plan(model_id, tensors)
     except NoSpace:
@@ -149,7 +153,7 @@ def replay(w):
     def load(name):
         tensors, hb = workload_descs(w, name)
         mid = w.models[name].model_id
-        lplan, oplan, _ = both_plan(pool, store, mid, tensors, hb)
+        lplan, oplan, _ = both_plan(pool, store, mid, tensors, None if w.streamed else hb)
         assert lplan is not None, "workload must fit its pool"
         assert_same_plan(lplan, oplan)
         tg.tg_commit(pool, lplan, len(tensors))
@@ -171,22 +175,12 @@ def replay(w):
         tg.tg_release(pool, mid, tg.TG_RELEASE_EVICT)
         store.release(mid, True)
 
-    if w.streamed:
-        # the parts of one model are loaded one after the other, then all released
-        for name in w.loads:
-            out[name] = load(name)
-            assert_same_stats(pool, store)
-        for name in w.loads:
-            evict(name)
+    for name in w.loads:
+        out[name] = load(name)
+        assert_same_stats(pool, store)
+        evict(name)
         assert store.stats() == out["stats_before"]
         assert_same_stats(pool, store)
-    else:
-        for name in w.loads:
-            out[name] = load(name)
-            assert_same_stats(pool, store)
-            evict(name)
-            assert store.stats() == out["stats_before"]
-            assert_same_stats(pool, store)
     tg.tg_pool_destroy(pool)
     return out
 
@@ -232,26 +226,70 @@ def test_plan_parity_neox20b_fragmented_pool():
 
 @pytest.mark.parametrize("reuse", [0.0, 0.5, 0.9])
 def test_plan_parity_llama70b(reuse):
+    """Config 5 is one model of 723 tensors and one plan, made without a host image."""
     w = synth.workload_llama70b(reuse, 272 * 10**9)
     out = replay(w)
-    total = sum(w.models[n].nbytes for n in w.loads)
-    reused = sum(out[n].reused_bytes for n in w.loads)
-    transfer = sum(out[n].transfer_bytes for n in w.loads)
-    assert len(w.loads) == 3 and sum(len(w.models[n].tensors) for n in w.loads) == 723
-    assert reused + transfer == total
+    assert w.loads == ["M70"] and len(w.models["M70"].tensors) == 723
+    plan = out["M70"]
+    total = w.models["M70"].nbytes
+    assert plan.reused_bytes + plan.transfer_bytes == total
     assert 141.0e9 < total < 141.2e9
-    # the parts hold every tensor once, fit the Model Cache, and each has its share of the transfers
-    names = [t.name for n in w.loads for t in w.models[n].tensors]
-    assert len(set(names)) == 723
-    assert all(w.models[n].nbytes <= 50 * 10**9 for n in w.loads)
-    if reuse < 1.0:
-        share = [out[n].transfer_bytes / transfer for n in w.loads]
-        assert min(share) > 0.2, share
+    n_reused = sum(1 for op in plan.ops if op.kind == 0)
     if reuse == 0.0:
-        # nothing designated; later parts still find the all-ones norm gains of earlier parts
-        assert reused == sum(t.nbytes for n in w.loads[1:] for t in w.models[n].tensors if t.kind == "ones")
+        # nothing is resident, so nothing is found: incoming tensors never match each other
+        assert n_reused == 0 and plan.reused_bytes == 0 and "sib" not in w.models
     else:
-        assert abs(reused / total - reuse) < 0.02
+        assert abs(plan.reused_bytes / total - reuse) < 0.02
+        # every designated tensor is found, and so are the all-ones norm gains of the other layers
+        ones = sum(1 for t, (nm, _, _) in zip(w.models["M70"].tensors, synth.llama_tensors(**synth.LLAMA70B_SHAPES))
+                   if t.kind == "ones")
+        assert w.designated_shared["M70"] <= n_reused <= w.designated_shared["M70"] + ones
+
+
+def test_plan_parity_llama70b_sweep_against_one_pool():
+    """The benchmark's arrangement: one pool holding the 90 % sibling, the three reuse levels in turn."""
+    w = synth.workload_llama70b_sweep(272 * 10**9)
+    out = replay(w)
+    for name, lo, hi in (("M70-90", 0.88, 0.92), ("M70-50", 0.48, 0.52), ("M70-0", 0.0, 0.0001)):
+        plan = out[name]
+        total = w.models[name].nbytes
+        assert plan.reused_bytes + plan.transfer_bytes == total
+        assert lo <= plan.reused_bytes / total <= hi, name
+
+
+def test_plan_without_a_host_image_and_its_argument_checks():
+    pool = tg.tg_pool_create(FAKE_BASE, 1 << 20, 256)
+    store = ReuseStoreOracle(1 << 20, 256)
+    # src_off is the caller's own reference when there is no image: any value is echoed back
+    tensors = [(512, 11, 1 << 50), (700, 12, 7), (512, 11, 99)]
+    lplan, oplan, _ = both_plan(pool, store, 1, tensors, None)
+    assert_same_plan(lplan, oplan)
+    assert [r[2] for r in rows_of(lplan)[0]] == [1 << 50, 7, 99]
+    # a whole-image assemble of a plan that has no image is refused before anything happens
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_assemble(pool, lplan, 3)
+    assert e.value.status == tg.TG_ERR_INVALID
+    assert_same_stats(pool, store)
+    tg.tg_plan_free(lplan)
+    # confirmation needs bytes to compare with
+    desc = tg.ModelDesc(2, 0, 0, tensors)
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_plan(pool, desc, tg.TG_PLAN_CONFIRM)
+    assert e.value.status == tg.TG_ERR_INVALID
+    # a length without a base is a mistake
+    bad = tg.ModelDesc(3, 0, 4096, tensors)
+    with pytest.raises(tg.TgError) as e:
+        tg.tg_plan(pool, bad)
+    assert e.value.status == tg.TG_ERR_INVALID
+    # the calls of a load in steps need a load that has begun
+    lplan = tg.tg_plan(pool, desc)
+    for call in (lambda: tg.tg_assemble_wait(pool, lplan, 3), lambda: tg.tg_assemble_feed_wait(pool, lplan, 0),
+                 lambda: tg.tg_assemble_feed(pool, lplan, FAKE_HOST, 4096, [(0, 0)])):
+        with pytest.raises(tg.TgError) as e:
+            call()
+        assert e.value.status == tg.TG_ERR_INVALID
+    tg.tg_plan_free(lplan)
+    tg.tg_pool_destroy(pool)
 
 
 def test_error_paths_leave_the_pool_unchanged():
