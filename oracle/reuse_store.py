@@ -25,16 +25,22 @@ ones the product documents):
     read, can be evicted; ties in cost go to the lower offset; a tensor that
     several models own costs the sum of its owners' costs;
   * Stage 2 runs only when plain best fit fails.  A subspace's capacity for
-    new tensors is its free bytes (the text counts allocated bytes too, which
-    would hand a subspace more than it can hold after merging); partition
-    points are tried in order of descending gain (ties: lower offset); the
-    packing test is the listing's: a tensor must be smaller than the smaller
-    bin's remaining capacity, and goes to the bin with more room (ties: the
-    first) -- the text words the test differently (the tensor only has to fit
-    the bin with more room), which is available as ``pack_text``; regions in use by a running model cannot move and split the pool
-    before the algorithm starts (there a tensor goes to the side with more
-    room and only has to fit it); a final subspace first tries plain best fit
-    inside itself and is compacted towards its low end only if that fails;
+    new tensors is its free bytes; the text counts allocated bytes too, which
+    can hand a subspace more than it holds after merging -- that reading is
+    available as ``cap_text`` and makes the plan fail when it happens.
+    Partition points are tried in order of descending gain (ties: lower
+    offset).  The packing test is the listing's: a tensor must be smaller than
+    the smaller bin's remaining capacity, and goes to the bin with more room
+    (ties: the first); the text words the test differently (the tensor only
+    has to fit the bin with more room), which is available as ``pack_text``.
+    Regions in use by a running model cannot move: they cut the pool into
+    subspaces that cannot be merged with each other, and the tensors are dealt
+    over those by the text's packing rule (largest remaining space first)
+    before Algorithm 1 runs inside each.  The merge cost reported is the sum of
+    the allocated bytes inside the final subspaces that were given tensors;
+    the listing's running M also keeps counting regions that have dropped out
+    of every subspace.  A final subspace first tries plain best fit inside
+    itself and is compacted towards its low end only if that fails;
   * if the tensors cannot be placed the plan fails and nothing changes.
 """
 from dataclasses import dataclass, field
@@ -168,112 +174,115 @@ def try_packing(sizes: Sequence[int], tensors: List[int], c1: int, c2: int
     return t1, t2
 
 
-def split_at_wall(sizes: Sequence[int], tensors: List[int], c1: int, c2: int
-                  ) -> Optional[Tuple[List[int], List[int]]]:
-    """Tensors (descending size) over the two sides of a region that cannot
-    move: each goes to the side with more room left (ties: the first) and the
-    split fails only if it does not fit there.  Not part of Algorithm 1, which
-    assumes every resident tensor may move."""
-    t1: List[int] = []
-    t2: List[int] = []
-    for k in tensors:
-        if c1 >= c2:
-            if sizes[k] > c1:
-                return None
-            t1.append(k)
-            c1 -= sizes[k]
-        else:
-            if sizes[k] > c2:
-                return None
-            t2.append(k)
-            c2 -= sizes[k]
-    return t1, t2
-
-
-def trim(regions: List[List], lo: int, hi: int) -> Optional[Tuple[int, int]]:
-    """Largest sub-range of regions[lo:hi] that begins and ends with a free
-    region (a subspace), or None."""
-    while lo < hi and not regions[lo][2]:
-        lo += 1
-    while hi > lo and not regions[hi - 1][2]:
-        hi -= 1
-    return (lo, hi) if lo < hi else None
-
-
-def free_bytes_of(regions: List[List], sub: Optional[Tuple[int, int]]) -> int:
-    if sub is None:
-        return 0
-    return sum(r[1] for r in regions[sub[0]:sub[1]] if r[2])
-
-
 def try_packing_text(sizes: Sequence[int], tensors: List[int], c1: int, c2: int
                      ) -> Tuple[List[int], List[int]]:
     """TryPacking as the text of Section 3.2 words it (the listing and the text
-    differ): a tensor goes to the bin with the largest remaining space and the
-    attempt fails only if it does not fit into that bin."""
-    parts = split_at_wall(sizes, tensors, c1, c2)
-    return ([], []) if parts is None else parts
+    differ): a tensor goes to the bin with the largest remaining space (ties:
+    the first) and the attempt fails only if it does not fit into that bin."""
+    bins = ([], [])
+    room = [c1, c2]
+    for k in tensors:
+        b = 0 if room[0] >= room[1] else 1
+        if sizes[k] > room[b]:
+            return [], []
+        bins[b].append(k)
+        room[b] -= sizes[k]
+    return bins
 
 
-def partitioned_gain_packing(regions: List[List], sizes: Sequence[int], order: List[int],
-                             movable, pack=try_packing
-                             ) -> Optional[Tuple[List[Tuple[Tuple[int, int], List[int]]], int]]:
-    """Algorithm 1.  `regions` is the Region List, `order` the new tensors in
-    descending size, `movable(region)` tells whether an allocated region may
-    move.  Returns (allocation set A as ((lo, hi), tensor subset) pairs in
-    address order, merge cost M) or None when the tensors cannot be split over
-    the parts of the pool that immovable regions separate."""
-    whole = trim(regions, 0, len(regions))
-    if whole is None:
-        return None
-    # Regions that cannot move cut the pool into independent stretches first.
-    pending: List[Tuple[Tuple[int, int], List[int]]] = []
-    sub, tensors = whole, list(order)
-    while True:
-        wall = next((i for i in range(sub[0], sub[1])
-                     if not regions[i][2] and not movable(regions[i])), None)
-        if wall is None:
-            pending.append((sub, tensors))
-            break
-        p1, p2 = trim(regions, sub[0], wall), trim(regions, wall + 1, sub[1])
-        parts = split_at_wall(sizes, tensors, free_bytes_of(regions, p1), free_bytes_of(regions, p2))
-        if parts is None:
-            return None
-        t1, t2 = parts
-        if p1 is not None:
-            pending.append((p1, t1))
-        elif t1:
-            return None
-        if p2 is None:
-            if t2:
-                return None
-            break
-        sub, tensors = p2, t2
+def subspace(regions: List[List], lo: int, hi: int) -> Optional[Tuple[int, int]]:
+    """The subspace inside regions[lo:hi]: the longest run that begins and ends
+    with a free region (Section 3.2, "Partitioning subspaces"), or None."""
+    free = [i for i in range(lo, hi) if regions[i][2]]
+    return (free[0], free[-1] + 1) if free else None
 
-    merge = sum(r[1] for s, _ in pending for r in regions[s[0]:s[1]] if not r[2])
-    final: List[Tuple[Tuple[int, int], List[int]]] = []
+
+def free_bytes(regions: List[List], sub: Tuple[int, int]) -> int:
+    return sum(r[1] for r in regions[sub[0]:sub[1]] if r[2])
+
+
+def allocated_bytes(regions: List[List], sub: Tuple[int, int]) -> int:
+    """A subspace's maximum merge cost M: the bytes of its allocated regions."""
+    return sum(r[1] for r in regions[sub[0]:sub[1]] if not r[2])
+
+
+def capacity(regions: List[List], sub: Optional[Tuple[int, int]], as_printed: bool) -> int:
+    """What a subspace can take of new tensors.  The text defines C as free plus
+    allocated bytes (`as_printed`); the allocated regions stay where they are
+    or move inside the subspace, so only the free bytes can really be handed
+    out, and that is the default here."""
+    if sub is None:
+        return 0
+    return free_bytes(regions, sub) + (allocated_bytes(regions, sub) if as_printed else 0)
+
+
+def partitioned_gain_packing(regions: List[List], pairs: List[Tuple[Tuple[int, int], List[int]]],
+                             sizes: Sequence[int], pack=try_packing, cap_as_printed: bool = False
+                             ) -> Tuple[List[Tuple[Tuple[int, int], List[int]]], int]:
+    """Algorithm 1.  `pairs` is the pending set P to start from -- (subspace,
+    tensor subset) pairs, each subset in descending size; the listing starts
+    with the single pair (R, T).  Returns (allocation set A in address order,
+    the listing's running merge cost M: all allocated bytes of the starting
+    subspaces minus the size of every partition point taken)."""
+    pending = list(pairs)
+    m = sum(allocated_bytes(regions, sub) for sub, _t in pending)
+    done: List[Tuple[Tuple[int, int], List[int]]] = []
     while pending:
         nxt: List[Tuple[Tuple[int, int], List[int]]] = []
         for sub, tensors in pending:
             points = [i for i in range(sub[0], sub[1]) if not regions[i][2]]
-            points.sort(key=lambda i: (-regions[i][1], regions[i][0]))   # largest gain first
-            split = False
+            # partition gain = the point's size; the largest gain is tried first (ties: lower offset)
+            points.sort(key=lambda i: (-regions[i][1], regions[i][0]))
+            split_occurred = False
             for p in points:
-                p1, p2 = trim(regions, sub[0], p), trim(regions, p + 1, sub[1])
-                t1, t2 = pack(sizes, tensors, free_bytes_of(regions, p1), free_bytes_of(regions, p2))
+                p1, p2 = subspace(regions, sub[0], p), subspace(regions, p + 1, sub[1])
+                t1, t2 = pack(sizes, tensors, capacity(regions, p1, cap_as_printed),
+                              capacity(regions, p2, cap_as_printed))
                 if t1 or t2:
-                    if p1 is not None:
-                        nxt.append((p1, t1))
-                    if p2 is not None:
-                        nxt.append((p2, t2))
-                    merge -= regions[p][1]
-                    split = True
+                    split_occurred = True
+                    nxt += [(p1, t1), (p2, t2)]
+                    m -= regions[p][1]
                     break
-            if not split:
-                final.append((sub, tensors))
+            if not split_occurred:
+                done.append((sub, tensors))
         pending = nxt
-    final.sort(key=lambda st: st[0][0])
-    return final, merge
+    done.sort(key=lambda st: st[0][0])
+    return done, m
+
+
+def stretches(regions: List[List], movable) -> List[Tuple[int, int]]:
+    """The pool cut at every allocated region that may not move (tensors of
+    running models): the subspaces between them, in address order.  Algorithm 1
+    assumes every resident tensor may move; this is what is left of its
+    starting subspace R when some may not."""
+    out = []
+    lo = 0
+    for i, r in enumerate(regions + [None]):
+        if r is None or (not r[2] and not movable(r)):
+            sub = subspace(regions, lo, i)
+            if sub is not None:
+                out.append(sub)
+            lo = i + 1
+    return out
+
+
+def deal_over_stretches(regions: List[List], subs: List[Tuple[int, int]], sizes: Sequence[int],
+                        order: List[int], cap_as_printed: bool) -> Optional[List[List[int]]]:
+    """The new tensors (descending size) over several subspaces that cannot be
+    merged with each other: each goes to the subspace with the largest
+    remaining space (ties: lowest address) -- the packing rule of Section 3.2
+    with as many bins as there are subspaces -- and None if one does not fit."""
+    room = [capacity(regions, sub, cap_as_printed) for sub in subs]
+    subsets: List[List[int]] = [[] for _ in subs]
+    for k in order:
+        if not room:
+            return None
+        b = max(range(len(room)), key=lambda i: (room[i], -i))
+        if sizes[k] > room[b]:
+            return None
+        subsets[b].append(k)
+        room[b] -= sizes[k]
+    return subsets
 
 
 class ReuseStoreOracle:
@@ -342,7 +351,8 @@ class ReuseStoreOracle:
     # ------------------------------------------------------------------- plan
     def plan(self, model_id: int, tensors: Sequence[Tuple[int, int, int]],
              host: Optional[np.ndarray] = None, confirm: bool = False, evict: bool = False,
-             merge: bool = False, alias: bool = False, pack_text: bool = False) -> OraclePlan:
+             merge: bool = False, alias: bool = False, pack_text: bool = False,
+             cap_text: bool = False) -> OraclePlan:
         """``tensors[k] = (nbytes, fp, host_off)``.  Pure: the store is not
         modified; the result records everything the commit will install."""
         if model_id in self.models and self.models[model_id]["active"]:
@@ -403,12 +413,20 @@ class ReuseStoreOracle:
         else:
             # ---- Stage 2: Partitioned-Gain Packing (Algorithm 1)
             dsts = {}
-            res = partitioned_gain_packing(regions, sizes, order,
-                                           lambda r: r[3] is not None and r[3].active_refs == 0,
-                                           try_packing_text if pack_text else try_packing)
-            if res is None:
+            subs = stretches(regions, lambda r: r[3].active_refs == 0)
+            subsets = deal_over_stretches(regions, subs, sizes, order, cap_text)
+            if subsets is None:
                 raise NoSpace("running models' tensors separate the free space")
-            final, merge_bound = res
+            final, _m_listing = partitioned_gain_packing(
+                regions, list(zip(subs, subsets)), sizes,
+                try_packing_text if pack_text else try_packing, cap_text)
+            # Only subspaces that were given tensors can have anything merged in them.
+            final = [(sub, subset) for sub, subset in final if subset]
+            merge_bound = sum(allocated_bytes(regions, sub) for sub, _t in final)
+            for sub, subset in final:
+                if sum(sizes[k] for k in subset) > free_bytes(regions, sub):
+                    # only with the capacity as printed: allocated bytes were counted as room
+                    raise NoSpace("a subspace was handed more than its free bytes")
             # realise the subspaces from the high end down so list indices stay valid
             realised = []
             for (lo, hi), subset in reversed(final):

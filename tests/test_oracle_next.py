@@ -17,7 +17,8 @@ import pytest
 
 import oracle
 from oracle import H2D, REUSE, NoSpace, ReuseStoreOracle
-from oracle.reuse_store import partitioned_gain_packing, try_packing, try_packing_text
+from oracle.reuse_store import (allocated_bytes, deal_over_stretches, free_bytes, partitioned_gain_packing, stretches,
+                                 subspace, try_packing, try_packing_text)
 
 U = 256
 
@@ -199,21 +200,240 @@ def regions_of(units):
     return out
 
 
-def test_packing_example_of_the_paper():
+@pytest.mark.parametrize("cap_as_printed", [False, True])
+def test_packing_example_of_the_paper(cap_as_printed):
     # One unit of the paper's example = 2 * 256 bytes here.  Free 2, A (gain 1),
     # free 2, B (gain 3), free 4:  C = 12, M = 4.
     regs = regions_of([(4, True), (2, False), (4, True), (6, False), (8, True)])
-    assert sum(r[1] for r in regs) == 12 * 2 * U
-    assert sum(r[1] for r in regs if not r[2]) == 4 * 2 * U
+    whole = subspace(regs, 0, len(regs))
+    assert whole == (0, 5)
+    assert free_bytes(regs, whole) + allocated_bytes(regs, whole) == 12 * 2 * U      # C
+    assert allocated_bytes(regs, whole) == 4 * 2 * U                                # M
     sizes = [6 * U, 1 * U]
-    final, m = partitioned_gain_packing(regs, sizes, [0, 1], lambda r: True)
+    seen = []
+
+    def watched(sz, tensors, c1, c2):
+        seen.append((c1 // U, c2 // U))
+        return try_packing(sz, tensors, c1, c2)
+    final, m = partitioned_gain_packing(regs, [(whole, [0, 1])], sizes, watched, cap_as_printed)
     # the point with gain 3 is tried first and succeeds: M = 4 -> 1; the left
     # subspace keeps its tensor and cannot be split at the gain-1 point (6 is
     # not smaller than 4); the right one has no allocated region left
     assert m == 1 * 2 * U
     assert final == [((0, 3), [0]), ((4, 5), [1])]
+    # what reached the packing test: first the two sides of the gain-3 point, then those of the
+    # gain-1 point.  With the capacity as the text defines it the sides of the first point and the
+    # point itself make up C = 12 (paper units); by free bytes alone they make up C - M = 8.
+    if cap_as_printed:
+        assert seen == [(10, 8), (4, 4)] and seen[0][0] + seen[0][1] + 6 == 12 * 2
+    else:
+        assert seen == [(8, 8), (4, 4)] and seen[0][0] + seen[0][1] == (12 - 4) * 2
     # had the gain-1 point been tried first it would have failed:
     assert try_packing(sizes, [0, 1], 4 * U, 12 * U) == ([], [])
+
+
+def test_capacity_as_printed_can_hand_a_subspace_more_than_it_holds():
+    # Units of 256 B:  F2 A10 F2 b1 F6  (21 units, 10 free).  Incoming 5 and 4 (9 <= 10 free), text's
+    # packing test.  Best fit fails (after 5 -> F6 no hole holds 4).
+    # By free bytes: at A (gain 10) the sides hold 2 and 8: 5 -> right (3 left), 4 fits neither: no.
+    #   At b (gain 1) they hold 4 and 6: 5 -> right, 4 -> left: split.  Left {4}: A slides 2 -> 0, the
+    #   4 lands behind it at 10; right {5} goes straight into F6 at 15.  M = 10 (A may move).
+    # By the printed capacity (free + allocated): at A the sides "hold" 2 and 2 + 1 + 6 = 9: 5 -> right
+    #   (4 left), 4 -> right: accepted -- but the right side has 8 free bytes for 9 bytes of tensors,
+    #   and splitting it at b cannot help (5 -> F6, 4 > 2).  No placement exists inside it.
+    rnd = random.Random(11)
+
+    def fresh():
+        s = ReuseStoreOracle(21 * U)
+        carve_layout(s, rnd, [(2, False), (10, True), (2, False), (1, True), (6, False)])
+        assert [(r[1] // U, r[2]) for r in s.regions] == [(2, True), (10, False), (2, True), (1, False), (6, True)]
+        return s
+    new = [rb(rnd, 5 * U), rb(rnd, 4 * U)]
+    host, offs = pack(new)
+    s = fresh()
+    with pytest.raises(NoSpace):
+        s.plan(9, rows(new, offs), host)
+    plan = s.plan(9, rows(new, offs), host, merge=True, pack_text=True)
+    assert [(o // U, n // U) for _e, o, n in plan.moves] == [(2, 0)]
+    assert [op.dst_off // U for op in plan.ops] == [15, 10]
+    assert plan.merge_bound == 10 * U and plan.moved_bytes == 10 * U
+    with pytest.raises(NoSpace):
+        fresh().plan(9, rows(new, offs), host, merge=True, pack_text=True, cap_text=True)
+    # where nothing is over-committed the two capacities plan alike: the hand-derived merge example
+    layout = [(4, False), (2, True), (4, False), (6, True), (4, False), (1, True), (4, False), (1, True), (4, False)]
+    new = [rb(rnd, 6 * U), rb(rnd, 5 * U - 7)]
+    host, offs = pack(new)
+    plans = []
+    for cap_text in (False, True):
+        s = ReuseStoreOracle(30 * U)
+        carve_layout(s, rnd, layout)
+        plans.append(s.plan(9, rows(new, offs), host, merge=True, cap_text=cap_text))
+    assert [op.dst_off for op in plans[0].ops] == [op.dst_off for op in plans[1].ops]
+    assert [(o, n) for _e, o, n in plans[0].moves] == [(o, n) for _e, o, n in plans[1].moves]
+
+
+def test_regions_that_cannot_move_cut_the_pool_into_subspaces():
+    # F3 w1 F2 a1 F4 w1 w1 F5 a2 (w: running, cannot move; a: retained)
+    regs = regions_of([(3, True), (1, False), (2, True), (1, False), (4, True), (1, False), (1, False), (5, True),
+                       (2, False)])
+    walls = {1, 5, 6}
+    for i in walls:
+        regs[i][3] = "wall"
+    subs = stretches(regs, lambda r: r[3] != "wall")
+    assert subs == [(0, 1), (2, 5), (7, 8)]           # the trailing retained tensor is outside every subspace
+    assert [free_bytes(regs, x) // U for x in subs] == [3, 6, 5]
+    sizes = [u * U for u in (5, 4, 3, 1, 1)]
+    # each tensor to the subspace with the most room left (ties: lowest address):
+    # 5 -> middle (6 -> 1); 4 -> last (5 -> 1); 3 -> first (3 -> 0); 1 -> middle (tie 1 = 1: lower address); 1 -> last
+    assert deal_over_stretches(regs, subs, sizes, [0, 1, 2, 3, 4], False) == [[2], [0, 3], [1, 4]]
+    assert deal_over_stretches(regs, subs, [6 * U, 6 * U], [0, 1], False) is None       # the second 6 fits nowhere
+    assert deal_over_stretches(regs, [], sizes, [0], False) is None
+    # by the printed capacity the middle subspace counts its retained tensor as room: 7
+    assert deal_over_stretches(regs, subs, [7 * U], [0], True) == [[], [0], []]
+
+
+# An independent statement of the two packing tests, for the checks below: written as a search for
+# the first tensor that breaks the rule rather than as the listing's loop.
+def packs(sizes, tensors, c1, c2, text):
+    room = [c1, c2]
+    sides = ([], [])
+    for k in tensors:
+        b = 0 if room[0] >= room[1] else 1
+        ok = sizes[k] <= room[b] if text else sizes[k] < min(room)
+        if not ok:
+            return None
+        sides[b].append(k)
+        room[b] -= sizes[k]
+    return sides if (sides[0] or sides[1]) else None
+
+
+def consistent_tree(regs, finals, sizes, text):
+    """True if the final subspaces `finals` (address order, those of one starting subspace) can have
+    come from splitting their union at allocated regions, each split passing the packing test with
+    exactly the tensor subsets found on its two sides."""
+    if len(finals) == 1:
+        return True
+    lo, hi = finals[0][0][0], finals[-1][0][1]
+    order = sorted((k for _s, t in finals for k in t), key=lambda k: (-sizes[k], k))
+    for cut in range(1, len(finals)):
+        left, right = finals[:cut], finals[cut:]
+        between = [i for i in range(left[-1][0][1], right[0][0][0]) if not regs[i][2]]
+        for p in between:
+            p1, p2 = subspace(regs, lo, p), subspace(regs, p + 1, hi)
+            if p1 != (lo, left[-1][0][1]) or p2 != (right[0][0][0], hi):
+                continue
+            got = packs(sizes, order, free_bytes(regs, p1), free_bytes(regs, p2), text)
+            want = (sorted(k for _s, t in left for k in t), sorted(k for _s, t in right for k in t))
+            if got is not None and (sorted(got[0]), sorted(got[1])) == want:
+                if consistent_tree(regs, left, sizes, text) and consistent_tree(regs, right, sizes, text):
+                    return True
+    return False
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_algorithm_1_on_random_small_pools_structure_independent_checks(seed):
+    """What must hold of Algorithm 1's result whatever the code that produced it looks like."""
+    rnd = random.Random(7000 + seed)
+    text = seed % 2 == 1
+    units = []
+    for _ in range(rnd.randrange(5, 16)):
+        units.append((rnd.randrange(1, 6), True))
+        for _ in range(rnd.randrange(1, 3)):                # sometimes two residents back to back
+            units.append((rnd.randrange(1, 7), False))
+    units.append((rnd.randrange(1, 6), True))
+    regs = regions_of(units)
+    whole = subspace(regs, 0, len(regs))
+    total_free = free_bytes(regs, whole)
+    sizes, left = [], total_free
+    while left >= U and len(sizes) < 8:
+        n = rnd.randrange(1, max(2, left // U // 2 + 1)) * U
+        sizes.append(n)
+        left -= n
+    order = sorted(range(len(sizes)), key=lambda k: (-sizes[k], k))
+    final, m_listing = partitioned_gain_packing(regs, [(whole, order)], sizes,
+                                                try_packing_text if text else try_packing)
+    # the allocation set covers every tensor once, its subspaces lie in address order, do not overlap,
+    # and each begins and ends with a free region
+    assert sorted(k for _s, t in final for k in t) == list(range(len(sizes)))
+    for (a, _ta), (b, _tb) in zip(final, final[1:]):
+        assert a[1] <= b[0]
+    for sub, subset in final:
+        assert regs[sub[0]][2] and regs[sub[1] - 1][2]
+        assert subset == sorted(subset, key=lambda k: (-sizes[k], k))      # sorted once, order kept
+        # every subset fits the free bytes of its subspace
+        assert sum(sizes[k] for k in subset) <= free_bytes(regs, sub)
+    # the bound: what can move at all lies inside the subspaces that were given tensors; the listing's
+    # running M never falls below that, and never exceeds merging everything
+    inside = sum(allocated_bytes(regs, sub) for sub, subset in final if subset)
+    assert inside <= m_listing <= allocated_bytes(regs, whole)
+    gone = sum(r[1] for i, r in enumerate(regs) if not r[2] and not any(s[0] <= i < s[1] for s, _t in final))
+    empty = sum(allocated_bytes(regs, sub) for sub, subset in final if not subset)
+    taken = allocated_bytes(regs, whole) - m_listing                        # sizes of the points taken
+    assert m_listing - inside == empty + (gone - taken)
+    # every split that led here passes the packing test with exactly these subsets ...
+    assert consistent_tree(regs, final, sizes, text)
+    # ... and no final subspace that holds tensors can be split any further
+    for sub, subset in final:
+        for p in range(sub[0], sub[1]):
+            if subset and not regs[p][2]:
+                p1, p2 = subspace(regs, sub[0], p), subspace(regs, p + 1, sub[1])
+                assert packs(sizes, subset, free_bytes(regs, p1), free_bytes(regs, p2), text) is None
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_merge_plans_on_random_small_pools_keep_their_promises(seed):
+    """Whole plans: moved bytes <= merge bound <= merge-all; moves only shift towards lower
+    addresses and never cross a running tensor; residents that do not move stay where they were."""
+    rnd = random.Random(9000 + seed)
+    s = ReuseStoreOracle(64 * U)
+    layout = []
+    for _ in range(rnd.randrange(4, 12)):
+        layout.append((rnd.randrange(1, 5), False))
+        layout.append((rnd.randrange(1, 5), True))
+    total = sum(u for u, _k in layout)
+    if total > 60:
+        pytest.skip("layout does not fit")
+    layout.append((64 - total, False))
+    kept = carve_layout(s, rnd, layout)
+    running = []
+    for i, (mid, t) in sorted(kept.items()):
+        if rnd.random() < 0.25:                    # some residents are running: they cannot move
+            host_w, offs_w = pack([t])
+            s.assemble(s.plan(mid, rows([t], offs_w), host_w, alias=True), host_w)
+            running.append(next(e for e in s.entries if e.owners == [mid]))
+    free = s.stats()["free_bytes"]
+    new = []
+    while free >= 4 * U and len(new) < 5:
+        n = rnd.randrange(1, max(2, free // U // 2)) * U
+        new.append(rb(rnd, n - rnd.randrange(0, 9)))
+        free -= n
+    if not new:
+        pytest.skip("pool is full")
+    host, offs = pack(new)
+    flags = dict(merge=True, pack_text=seed % 2 == 0)
+    before = [list(r) for r in s._regions]
+    try:
+        plan = s.plan(9, rows(new, offs), host, **flags)
+    except NoSpace:
+        return
+    merge_all = sum(r[1] for r in before if not r[2])
+    assert plan.moved_bytes <= sum(-(-e.nbytes // U) * U for e, _o, _n in plan.moves) <= plan.merge_bound <= merge_all
+    walls = sorted(e.off for e in running)
+    for e, old, to in plan.moves:
+        assert e.active_refs == 0 and to < old
+        assert not any(to < w < old for w in walls)
+    # nothing outside the stretch of addresses between two running tensors that a move touches has changed
+    after = {r[0]: r for r in plan.regions_after if not r[2] and r[3] is not None and not isinstance(r[3], tuple)}
+    moved_ids = {id(e) for e, _o, _n in plan.moves}
+    for r in before:
+        if not r[2] and id(r[3]) not in moved_ids and not any(e is r[3] for e in plan.evictions):
+            assert r[0] in after and after[r[0]][3] is r[3]
+    dsts = s.assemble(plan, host)
+    for t, d in zip(new, dsts):
+        assert s.image[d][:len(t)].tobytes() == t.tobytes()
+    for mid, t in kept.values():
+        es = [e for e in s.entries if mid in e.owners]
+        assert len(es) == 1 and s.image[es[0].off][:len(t)].tobytes() == t.tobytes()
 
 
 def test_hand_derived_merge_plan():

@@ -218,8 +218,10 @@ def test_a_wrong_store_function_fails_a_hand_derived_pin(case, monkeypatch):
     for mod in (nxt, st):
         if getattr(mod, attr, None) is original:
             monkeypatch.setattr(mod, attr, wrong)
-    if rs.partitioned_gain_packing.__defaults__ == (original,):
-        monkeypatch.setattr(rs.partitioned_gain_packing, "__defaults__", (wrong,))
+    defaults = rs.partitioned_gain_packing.__defaults__
+    if any(d is original for d in defaults):
+        monkeypatch.setattr(rs.partitioned_gain_packing, "__defaults__",
+                            tuple(wrong if d is original else d for d in defaults))
     caught = 0
     for pin in pins:
         try:
