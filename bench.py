@@ -265,6 +265,8 @@ def bench_resident(args, torch, w, link_peak, steps, warmup, with_extras, with_c
 
     r = WorkloadRunner(w, "cuda:0", log=log)
     r.pool.set_profiling(True)
+    if args.tune:
+        r.pool.set_tuning(**{k: int(v) for k, v in (kv.split("=") for kv in args.tune.split(","))})
     r.run_setup()
     for name in w.loads:
         r.materialise(name)
@@ -468,6 +470,8 @@ def bench_llama70b(args, torch, link_peak, levels, steps, warmup):
     log("workload %s: pool %.1f GB, loads %s" % (w.name, w.pool_bytes / 1e9, w.loads))
     r = WorkloadRunner(w, "cuda:0", log=log)
     r.pool.set_profiling(True)
+    if args.tune:
+        r.pool.set_tuning(**{k: int(v) for k, v in (kv.split("=") for kv in args.tune.split(","))})
     t0 = time.time()
     r.run_setup()
     log("resident sibling in place after %.1f s; pool: %s" % (time.time() - t0, r.pool.stats()))
@@ -556,6 +560,7 @@ def main():
                     help="also run one plain 1 GiB elementwise torch kernel (out = in * 1.0), so that a "
                          "rocprofv3 --pmc run has a kernel of known traffic to scale its counters by")
     ap.add_argument("--probe-alu", action="store_true", help="only measure the fingerprint's mix without loads")
+    ap.add_argument("--tune", default="", help="fields of tg_tuning to override, e.g. gather_wgs_per_cu=2,fuse_verify=0")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives are part of "

@@ -67,6 +67,7 @@ typedef int32_t tg_status;
 #define TG_PLAN_MERGE     4u   /* Stage 2: when best fit fails, pack by partitions and merge free regions */
 #define TG_PLAN_ALIAS     8u   /* a hit is used where it lies (no copy, no new slot) */
 #define TG_PLAN_PACK_TEXT 16u  /* Stage 2 packing test as the text words it (see tg_plan) */
+#define TG_PLAN_CAP_TEXT  32u  /* Stage 2 subspace capacity as the text defines it (see tg_plan) */
 /* tg_assemble flags */
 #define TG_ASSEMBLE_VERIFY 1u  /* fingerprint every assembled slot and compare with the descriptor */
 /* tg_release flags */
@@ -181,6 +182,7 @@ typedef struct {
     uint32_t feeds;           /* tg_assemble_feed calls (1 for a load from a whole host image) */
     uint64_t move_bytes;      /* bytes of the tensors moved */
     uint64_t move_traffic_bytes; /* bytes read + written by the move launches (staged stretches count twice) */
+    uint64_t fused_verify_bytes; /* bytes a verifying load fingerprinted inside its copy launches (not in verify_bytes) */
 } tg_timing;
 
 /*
@@ -241,7 +243,12 @@ tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint
  * threshold of Section 4: missing tensors that are adjacent both in the host
  * image and in the pool are merged into one copy until the copy exceeds this
  * many bytes (the paper's loader uses 8 MB); 0, the default, puts no limit on
- * a merged copy.  The defaults (tg_default_tuning) are the measured optimum on
+ * a merged copy.  fuse_verify (default 1) makes a verifying load compute the
+ * fingerprints of the tensors it copies device to device inside the gather
+ * launch, from the bytes as they pass through the registers, instead of
+ * reading the written slots again with a second launch (0): one pass over HBM
+ * less, and it vouches for what was read rather than for what was written.
+ * The defaults (tg_default_tuning) are the measured optimum on
  * MI355X; results never depend on these values.  A pool starts with the
  * defaults.
  */
@@ -251,6 +258,8 @@ typedef struct {
     uint32_t compare_unroll, compare_wgs_per_cu;
     uint64_t h2d_kernel_max_bytes;
     uint64_t h2d_group_bytes;
+    uint32_t fuse_verify;     /* 1: a verifying load fingerprints copied tensors inside the copy launch */
+    uint32_t reserved;        /* must be 0 */
 } tg_tuning;
 tg_status tg_default_tuning(tg_tuning *out);
 tg_status tg_pool_set_tuning(tg_pool *pool, const tg_tuning *t);
@@ -358,18 +367,25 @@ tg_status tg_compare_ex(const tg_pair *pairs, uint32_t n, uint32_t *out_differs,
  *           smallest free region that holds it (ties: lowest offset), at the
  *           region's low end.
  *  merge    with TG_PLAN_MERGE, when best fit fails although enough bytes are
- *           free: Algorithm 1 splits the Region List at resident tensors
- *           (largest first) wherever its two-bin packing test lets the tensors
- *           be divided over the two sides, by free bytes; each final subspace
- *           takes its tensors by best fit if it can, else its resident tensors
- *           are slid to its low end (tg_plan_moves) and the tensors placed in
- *           the merged free tail.  Tensors in use by a running model never
- *           move; they split the pool beforehand.  The packing test is the
+ *           free: Algorithm 1 cuts the Region List at resident tensors
+ *           (largest first) wherever its two-bin packing test lets the new
+ *           tensors be divided over the two sides; each final subspace that
+ *           was given tensors takes them by best fit if it can, else its
+ *           resident tensors are slid to its low end (tg_plan_moves) and the
+ *           tensors placed in the merged free tail.  merge_bound is the sum of
+ *           the resident bytes inside those subspaces.  Tensors in use by a
+ *           running model never move: they cut the pool into subspaces
+ *           beforehand, and each new tensor (largest first) goes to the one
+ *           with the most room left.  Two points where the paper's text and
+ *           its listing part ways are selectable.  The packing test is the
  *           listing's (a tensor must be smaller than the smaller bin's
- *           remaining room; it goes to the bin with more room); the paper's
- *           text words it differently (the tensor only has to fit the bin with
- *           more room), which TG_PLAN_PACK_TEXT selects and which splits far
- *           more often.
+ *           remaining room; it goes to the bin with more room); the text
+ *           lets the tensor merely fit the bin with more room, which
+ *           TG_PLAN_PACK_TEXT selects and which splits far more often.  A
+ *           subspace's room is its free bytes; the text defines its capacity
+ *           as free plus allocated bytes, which TG_PLAN_CAP_TEXT selects and
+ *           which can hand a subspace more than it can hold after merging --
+ *           the plan then fails with TG_ERR_NOSPACE.
  *
  * The pool is not modified.  *out receives a plan bound to the pool's current
  * generation.  TG_ERR_INVALID: null arguments, unknown flag bits, n_tensors ==

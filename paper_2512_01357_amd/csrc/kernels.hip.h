@@ -40,7 +40,9 @@ constexpr u64 kGamma = 0x9E3779B97F4A7C15ull;
 
 struct Span { u64 ptr, nbytes; };           // extent to fingerprint
 struct Pair { u64 a, b, nbytes; };          // extents to compare
-struct Copy { u64 dst, src, nbytes; };      // extent to copy (non-overlapping)
+// Extent to copy (non-overlapping).  A launch that also fingerprints what it copies adds the sum
+// over this extent's words to out[slot], the first word counting as word number word0 of its tensor.
+struct Copy { u64 dst, src, nbytes, word0; u32 slot, pad; };
 
 template <int T, int U> constexpr u64 tile_bytes() { return u64(T) * 16 * U; }
 
@@ -283,40 +285,131 @@ __global__ __launch_bounds__(T) void compare_kernel(const Pair *__restrict__ pai
 // while the current tile is being stored measured 2 % slower.  Unlike the
 // fingerprint, a copy carries nothing from tile to tile, so changing extent
 // costs one table look-up.
-template <int T, int U>
+//
+// With FP the launch also fingerprints every extent as it passes through the
+// registers (out[slot] += the sum over the extent's words; it vouches for the
+// bytes that were read).  A tile's arithmetic is put off by one turn of the
+// loop: it runs right after the loads of the next tile have been issued, so the
+// integer units work while those loads and the previous stores are in flight
+// instead of holding up the next loads.  The wave sums meet in LDS and lane 0
+// adds them up when it draws the next ticket: the loop has one single place
+// where one lane works alone, which keeps every barrier in control flow that
+// the whole workgroup walks in step.
+template <int T, int U, bool FP>
 __global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copies,
                                                     const u32 *__restrict__ prefix, u32 n_copies,
-                                                    u32 *__restrict__ ticket) {
+                                                    u32 *__restrict__ ticket, u64 *__restrict__ out) {
     constexpr u64 TILE = tile_bytes<T, U>();
+    constexpr u32 VPT = u32(T) * U;                // 16-byte vectors per tile
     __shared__ u32 next_tile;
+    __shared__ u64 wave_part[T / 64];
     const u32 tid = threadIdx.x;
     const u32 total = prefix[n_copies];
+    // FP: the tile of the previous turn, still in registers, and what its sum belongs to
+    u32x4 a[U];
+    u64 a_key = 0, a_extra = 0;
+    u32 a_nvec = 0, a_slot = 0;
+    bool have_a = false;
+    // FP: wave sums waiting in wave_part for lane 0
+    bool pending = false;
+    u32 pending_slot = 0;
     for (;;) {
-        if (tid == 0) next_tile = atomicAdd(ticket, 1u);
+        if (tid == 0) {
+            if (FP && pending) {
+                u64 sum = 0;
+#pragma unroll
+                for (int i = 0; i < T / 64; ++i) sum += wave_part[i];
+                atomicAdd(&out[pending_slot], sum);
+            }
+            next_tile = atomicAdd(ticket, 1u);
+        }
+        pending = false;
         __syncthreads();
         const u32 t = __builtin_amdgcn_readfirstlane(next_tile);
         __syncthreads();                           // every lane has read next_tile
-        if (t >= total) return;                    // workgroup-uniform
-        const u32 s = locate_first(prefix, n_copies, t);
-        const Copy cp = copies[s];
-        const u64 off = u64(t - prefix[s]) * TILE;
-        const u64 left = cp.nbytes - off;
-        const uint8_t *ps = reinterpret_cast<const uint8_t *>(cp.src) + off;
-        uint8_t *pd = reinterpret_cast<uint8_t *>(cp.dst) + off;
-        if (left >= TILE) {                        // workgroup-uniform
-            u32x4 v[U];
+        const bool more = t < total;               // workgroup-uniform
+        u32x4 b[U];
+        u64 b_key = 0, b_extra = 0;
+        u32 b_nvec = 0, b_slot = 0;
+        uint8_t *pd = nullptr;
+        if (more) {
+            const u32 s = locate_first(prefix, n_copies, t);
+            const Copy cp = copies[s];
+            const u64 off = u64(t - prefix[s]) * TILE;
+            const u64 left = cp.nbytes - off;
+            const uint8_t *ps = reinterpret_cast<const uint8_t *>(cp.src) + off;
+            pd = reinterpret_cast<uint8_t *>(cp.dst) + off;
+            if (left >= TILE) {                    // workgroup-uniform
+                b_nvec = VPT;
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = load16(ps + (u64(u) * T + tid) * 16);
-            __syncthreads();
+                for (int u = 0; u < U; ++u) b[u] = load16(ps + (u64(u) * T + tid) * 16);
+            } else {
+                b_nvec = u32(left / 16);
 #pragma unroll
-            for (int u = 0; u < U; ++u) store16(pd + (u64(u) * T + tid) * 16, v[u]);
-            __syncthreads();
-        } else {
-            const u64 nvec = left / 16;
-            for (u64 i = tid; i < nvec; i += T) store16(pd + i * 16, load16(ps + i * 16));
-            const u32 rem = u32(left % 16);
-            if (tid < rem) store1(pd + nvec * 16 + tid, load1(ps + nvec * 16 + tid));
+                for (int u = 0; u < U; ++u) {
+                    const u32 i = u32(u) * T + tid;
+                    b[u] = i < b_nvec ? load16(ps + u64(i) * 16) : u32x4{0, 0, 0, 0};
+                }
+                const u32 rem = u32(left % 16);    // ragged end of the extent: single bytes
+                if (tid < rem) store1(pd + u64(b_nvec) * 16 + tid, load1(ps + u64(b_nvec) * 16 + tid));
+                if (FP && rem != 0 && tid == 0) {  // at most two partial words
+                    const uint8_t *p = ps + u64(b_nvec) * 16;
+                    const u64 i0 = cp.word0 + off / 8 + 2 * u64(b_nvec);
+                    b_extra = mix(tail_word(p, rem) ^ (i0 * kGamma));
+                    if (rem > 8) b_extra += mix(tail_word(p + 8, rem - 8) ^ ((i0 + 1) * kGamma));
+                }
+            }
+            if (FP) {
+                b_key = (cp.word0 + off / 8 + 2 * u64(tid)) * kGamma;
+                b_slot = cp.slot;
+            }
         }
+        if (FP && have_a) {                        // the previous tile's sum, while this tile's loads fly
+            u64 acc = a_extra;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (u32(u) * T + tid < a_nvec) {
+                    const u64 k0 = a_key + u64(u) * (2 * T) * kGamma;
+                    acc += mix(lohi(a[u].x, a[u].y) ^ k0);
+                    acc += mix(lohi(a[u].z, a[u].w) ^ (k0 + kGamma));
+                }
+            }
+            const u64 ws = wave_sum(acc);
+            if ((tid & 63) == 0) wave_part[tid >> 6] = ws;
+            pending = true;
+            pending_slot = a_slot;
+            have_a = false;
+        }
+        __syncthreads();                           // the workgroup's loads are all issued; wave_part is complete
+        if (!more) {
+            if (FP && pending && tid == 0) {
+                u64 sum = 0;
+#pragma unroll
+                for (int i = 0; i < T / 64; ++i) sum += wave_part[i];
+                atomicAdd(&out[pending_slot], sum);
+            }
+            return;
+        }
+        if (b_nvec == VPT) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) store16(pd + (u64(u) * T + tid) * 16, b[u]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const u32 i = u32(u) * T + tid;
+                if (i < b_nvec) store16(pd + u64(i) * 16, b[u]);
+            }
+        }
+        if (FP) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) a[u] = b[u];
+            a_key = b_key;
+            a_extra = b_extra;
+            a_nvec = b_nvec;
+            a_slot = b_slot;
+            have_a = true;
+        }
+        __syncthreads();                           // the next tile's loads start after this tile's stores
     }
 }
 

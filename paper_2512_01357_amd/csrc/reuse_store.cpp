@@ -65,12 +65,18 @@ std::vector<RegionList::Flat> RegionList::flatten() const {
     return out;
 }
 
-void RegionList::rebuild(const std::vector<Flat> &flat) {
-    by_off_.clear();
-    free_idx_.clear();
-    free_bytes_ = 0;
-    for (const Flat &f : flat) {
-        by_off_.emplace_hint(by_off_.end(), f.off, Region{f.len, f.free, f.tag});
+// Replaces the regions that tile [start, end) by `flats` (which tile the same bytes).
+void RegionList::splice(uint64_t start, uint64_t end, const std::vector<Flat> &flats) {
+    auto it = by_off_.lower_bound(start);
+    while (it != by_off_.end() && it->first < end) {
+        if (it->second.free) {
+            free_idx_.erase({it->second.len, it->first});
+            free_bytes_ -= it->second.len;
+        }
+        it = by_off_.erase(it);
+    }
+    for (const Flat &f : flats) {
+        by_off_.emplace_hint(it, f.off, Region{f.len, f.free, f.tag});
         if (f.free) {
             free_idx_.insert({f.len, f.off});
             free_bytes_ += f.len;
@@ -78,160 +84,136 @@ void RegionList::rebuild(const std::vector<Flat> &flat) {
     }
 }
 
-// ------------------------------------------------------------------ Algorithm 1
+// ------------------------------------------------------------------ Stage 2
 namespace {
 
 using Flat = RegionList::Flat;
-struct Range { size_t lo = 0, hi = 0; bool ok = false; };
 
-// Largest sub-range of regs[lo, hi) that begins and ends with a free region.
-Range trim(const std::vector<Flat> &regs, size_t lo, size_t hi) {
-    while (lo < hi && !regs[lo].free) ++lo;
-    while (hi > lo && !regs[hi - 1].free) --hi;
-    Range r;
-    r.lo = lo;
-    r.hi = hi;
-    r.ok = lo < hi;
-    return r;
-}
+// Partitioned-Gain Packing (Section 3.2, Algorithm 1) over a snapshot of the
+// Region List.  Regions are addressed by index; byte counts of any index range
+// come from prefix sums, the subspace inside a range (its first to its last free
+// region) from two look-up arrays, so a partition attempt costs one pass over
+// the tensors and nothing over the regions.
+class Packer {
+public:
+    struct Piece { size_t lo, hi; std::vector<uint32_t> tensors; };      // regions [lo, hi) and what goes there
 
-uint64_t free_bytes_of(const std::vector<Flat> &regs, const Range &r) {
-    uint64_t f = 0;
-    if (r.ok)
-        for (size_t i = r.lo; i < r.hi; ++i)
-            if (regs[i].free) f += regs[i].len;
-    return f;
-}
-
-// TryPacking of Algorithm 1, as listed: tensors in descending size go to the
-// bin with more remaining capacity; fail as soon as one is not smaller than
-// the smaller remaining capacity.  Both outputs empty = failure.
-void try_packing(const std::vector<uint64_t> &sizes, const std::vector<uint32_t> &tensors, uint64_t c1,
-                 uint64_t c2, std::vector<uint32_t> &t1, std::vector<uint32_t> &t2) {
-    t1.clear();
-    t2.clear();
-    for (uint32_t k : tensors) {
-        if (sizes[k] >= std::min(c1, c2)) {
-            t1.clear();
-            t2.clear();
-            return;
+    Packer(const std::vector<Flat> &regs, const std::vector<uint64_t> &sizes, bool pack_text, bool cap_text)
+        : regs_(regs), sizes_(sizes), pack_text_(pack_text), cap_text_(cap_text) {
+        const size_t n = regs.size();
+        free_before_.assign(n + 1, 0);
+        used_before_.assign(n + 1, 0);
+        free_at_or_after_.assign(n + 1, n);
+        free_at_or_before_.assign(n + 1, n);
+        for (size_t i = 0; i < n; ++i) {
+            free_before_[i + 1] = free_before_[i] + (regs[i].free ? regs[i].len : 0);
+            used_before_[i + 1] = used_before_[i] + (regs[i].free ? 0 : regs[i].len);
         }
-        if (c1 >= c2) { t1.push_back(k); c1 -= sizes[k]; }
-        else          { t2.push_back(k); c2 -= sizes[k]; }
+        for (size_t i = n; i-- > 0;) free_at_or_after_[i] = regs[i].free ? i : free_at_or_after_[i + 1];
+        for (size_t i = 0; i < n; ++i) free_at_or_before_[i] = regs[i].free ? i : (i ? free_at_or_before_[i - 1] : n);
     }
-}
 
-// Either side of a region that cannot move: a tensor goes to the side with
-// more room and only has to fit there.  (Not part of Algorithm 1.)
-bool split_at_wall(const std::vector<uint64_t> &sizes, const std::vector<uint32_t> &tensors, uint64_t c1,
-                   uint64_t c2, std::vector<uint32_t> &t1, std::vector<uint32_t> &t2) {
-    t1.clear();
-    t2.clear();
-    for (uint32_t k : tensors) {
-        if (c1 >= c2) {
-            if (sizes[k] > c1) return false;
-            t1.push_back(k);
-            c1 -= sizes[k];
-        } else {
-            if (sizes[k] > c2) return false;
-            t2.push_back(k);
-            c2 -= sizes[k];
+    uint64_t free_bytes(size_t lo, size_t hi) const { return free_before_[hi] - free_before_[lo]; }
+    uint64_t used_bytes(size_t lo, size_t hi) const { return used_before_[hi] - used_before_[lo]; }
+
+    // The subspace inside [lo, hi): from its first to its last free region.  False if it has none.
+    bool narrow(size_t &lo, size_t &hi) const {
+        if (lo >= hi) return false;
+        const size_t first = free_at_or_after_[lo], last = free_at_or_before_[hi - 1];
+        if (first >= hi || last == regs_.size() || last < lo) return false;
+        lo = first;
+        hi = last + 1;
+        return true;
+    }
+
+    // What a range can be given: its free bytes, or free plus allocated bytes under the text's definition.
+    uint64_t room(bool ok, size_t lo, size_t hi) const {
+        if (!ok) return 0;
+        return free_bytes(lo, hi) + (cap_text_ ? used_bytes(lo, hi) : 0);
+    }
+
+    // Deals `tensors` (descending size) over two bins of room a and b: each goes to the bin with
+    // more room left (the first on ties).  side[i] = 0 or 1.  The listing refuses a tensor that is
+    // not smaller than the smaller bin's room; the text only one that does not fit its own bin.
+    bool two_bins(const std::vector<uint32_t> &tensors, uint64_t a, uint64_t b, std::vector<uint8_t> &side) const {
+        side.resize(tensors.size());
+        for (size_t i = 0; i < tensors.size(); ++i) {
+            const uint64_t need = sizes_[tensors[i]];
+            const bool second = a < b;
+            const bool refused = pack_text_ ? need > (second ? b : a) : need >= (second ? a : b);
+            if (refused) return false;
+            side[i] = second ? 1 : 0;
+            (second ? b : a) -= need;
         }
+        return true;
     }
-    return true;
-}
 
-// Algorithm 1.  `movable[i]` says whether allocated region i may move.
-// Returns false when immovable regions keep the tensors from being split.
-bool partitioned_gain_packing(const std::vector<Flat> &regs, const std::vector<uint64_t> &sizes,
-                              const std::vector<uint32_t> &order, const std::vector<char> &movable,
-                              bool pack_text, std::vector<Subspace> &final_set, uint64_t &merge_cost) {
-    final_set.clear();
-    Range whole = trim(regs, 0, regs.size());
-    if (!whole.ok) return false;
-    std::vector<Subspace> pending;
-    std::vector<uint32_t> t1, t2;
-    {
-        Range sub = whole;
-        std::vector<uint32_t> tensors = order;
-        for (;;) {
-            size_t wall = sub.hi;
-            for (size_t i = sub.lo; i < sub.hi; ++i)
-                if (!regs[i].free && !movable[i]) { wall = i; break; }
-            if (wall == sub.hi) {
-                pending.push_back(Subspace{sub.lo, sub.hi, tensors});
-                break;
-            }
-            const Range p1 = trim(regs, sub.lo, wall), p2 = trim(regs, wall + 1, sub.hi);
-            if (!split_at_wall(sizes, tensors, free_bytes_of(regs, p1), free_bytes_of(regs, p2), t1, t2))
-                return false;
-            if (p1.ok) pending.push_back(Subspace{p1.lo, p1.hi, t1});
-            else if (!t1.empty()) return false;
-            if (!p2.ok) {
-                if (!t2.empty()) return false;
-                break;
-            }
-            sub = p2;
-            tensors = t2;
+    // Starting pairs: the pool cut at every region that may not move; the tensors go to the
+    // piece with the most room left (lowest address on ties).  False if one fits nowhere.
+    bool deal(const std::vector<uint32_t> &order, const std::vector<char> &movable, std::vector<Piece> &out) const {
+        out.clear();
+        size_t lo = 0;
+        for (size_t i = 0; i <= regs_.size(); ++i) {
+            if (i < regs_.size() && (regs_[i].free || movable[i])) continue;
+            size_t a = lo, b = i;
+            if (narrow(a, b)) out.push_back(Piece{a, b, {}});
+            lo = i + 1;
         }
+        std::vector<uint64_t> left(out.size());
+        for (size_t j = 0; j < out.size(); ++j) left[j] = room(true, out[j].lo, out[j].hi);
+        for (uint32_t k : order) {
+            if (out.empty()) return false;
+            size_t best = 0;
+            for (size_t j = 1; j < out.size(); ++j)
+                if (left[j] > left[best]) best = j;
+            if (sizes_[k] > left[best]) return false;
+            out[best].tensors.push_back(k);
+            left[best] -= sizes_[k];
+        }
+        return true;
     }
-    merge_cost = 0;
-    for (const Subspace &s : pending)
-        for (size_t i = s.lo; i < s.hi; ++i)
-            if (!regs[i].free) merge_cost += regs[i].len;
 
-    std::vector<size_t> points;
-    while (!pending.empty()) {
-        std::vector<Subspace> next;
-        for (Subspace &s : pending) {
+    // Algorithm 1 on the starting pairs.  Pieces come back in address order, those without tensors
+    // left out.  A piece is cut at the largest allocated region (lowest address on ties) at which
+    // its tensors can be dealt over the two sides; what cannot be cut is final.
+    std::vector<Piece> run(std::vector<Piece> todo) const {
+        std::vector<Piece> done;
+        std::vector<size_t> points;
+        std::vector<uint8_t> side;
+        while (!todo.empty()) {
+            Piece cur = std::move(todo.back());
+            todo.pop_back();
+            if (cur.tensors.empty()) continue;                    // nothing to place: nothing to merge
             points.clear();
-            for (size_t i = s.lo; i < s.hi; ++i)
-                if (!regs[i].free) points.push_back(i);
-            // the partition gain of a point is its size: largest first, ties by offset
+            for (size_t i = cur.lo; i < cur.hi; ++i)
+                if (!regs_[i].free) points.push_back(i);
             std::stable_sort(points.begin(), points.end(),
-                             [&](size_t a, size_t b) { return regs[a].len > regs[b].len; });
-            bool split = false;
+                             [&](size_t x, size_t y) { return regs_[x].len > regs_[y].len; });
+            bool cut = false;
             for (size_t p : points) {
-                const Range p1 = trim(regs, s.lo, p), p2 = trim(regs, p + 1, s.hi);
-                // the listing's test, or the one the text words (a tensor only has to fit
-                // the bin with more room)
-                if (!pack_text) {
-                    try_packing(sizes, s.tensors, free_bytes_of(regs, p1), free_bytes_of(regs, p2), t1, t2);
-                } else if (!split_at_wall(sizes, s.tensors, free_bytes_of(regs, p1), free_bytes_of(regs, p2), t1, t2)) {
-                    t1.clear();
-                    t2.clear();
-                }
-                if (!t1.empty() || !t2.empty()) {
-                    if (p1.ok) next.push_back(Subspace{p1.lo, p1.hi, t1});
-                    if (p2.ok) next.push_back(Subspace{p2.lo, p2.hi, t2});
-                    merge_cost -= regs[p].len;
-                    split = true;
-                    break;
-                }
+                size_t l0 = cur.lo, l1 = p, r0 = p + 1, r1 = cur.hi;
+                const bool lok = narrow(l0, l1), rok = narrow(r0, r1);
+                if (!two_bins(cur.tensors, room(lok, l0, l1), room(rok, r0, r1), side)) continue;
+                Piece left{l0, l1, {}}, right{r0, r1, {}};
+                for (size_t i = 0; i < cur.tensors.size(); ++i) (side[i] ? right : left).tensors.push_back(cur.tensors[i]);
+                todo.push_back(std::move(left));
+                todo.push_back(std::move(right));
+                cut = true;
+                break;
             }
-            if (!split) final_set.push_back(std::move(s));
+            if (!cut) done.push_back(std::move(cur));
         }
-        pending.swap(next);
+        std::sort(done.begin(), done.end(), [](const Piece &a, const Piece &b) { return a.lo < b.lo; });
+        return done;
     }
-    std::sort(final_set.begin(), final_set.end(),
-              [](const Subspace &a, const Subspace &b) { return a.lo < b.lo; });
-    return true;
-}
 
-// Best fit restricted to a flat list (one subspace); carves like RegionList::take.
-bool best_fit_flat(std::vector<Flat> &part, uint64_t need, uint64_t tag, uint64_t &off) {
-    size_t pick = part.size();
-    for (size_t i = 0; i < part.size(); ++i) {
-        if (!part[i].free || part[i].len < need) continue;
-        if (pick == part.size() || part[i].len < part[pick].len) pick = i;
-    }
-    if (pick == part.size()) return false;
-    off = part[pick].off;
-    const uint64_t len = part[pick].len;
-    part[pick] = Flat{off, need, false, tag};
-    if (len > need) part.insert(part.begin() + pick + 1, Flat{off + need, len - need, true, 0});
-    return true;
-}
+private:
+    const std::vector<Flat> &regs_;
+    const std::vector<uint64_t> &sizes_;
+    const bool pack_text_, cap_text_;
+    std::vector<uint64_t> free_before_, used_before_;
+    std::vector<size_t> free_at_or_after_, free_at_or_before_;
+};
 
 }  // namespace
 
@@ -346,61 +328,67 @@ Status ReuseStore::plan(const std::vector<TensorIn> &tensors, const std::vector<
             return ERR_NOSPACE;
         } else {
             // ---- Stage 2: Partitioned-Gain Packing (Algorithm 1)
-            std::vector<Flat> regs = work.flatten();
+            const std::vector<Flat> regs = work.flatten();
             std::vector<char> movable(regs.size(), 0);
             for (size_t i = 0; i < regs.size(); ++i)
                 if (!regs[i].free) movable[i] = entries_.at(regs[i].tag).active_refs == 0;
-            std::vector<Subspace> final_set;
-            if (!partitioned_gain_packing(regs, sizes, order, movable, (flags & PLAN_PACK_TEXT) != 0, final_set,
-                                          plan.merge_bound))
-                return ERR_NOSPACE;
-            // realise the subspaces; the flat list is rebuilt piece by piece in address order
-            std::vector<Flat> out;
-            out.reserve(regs.size() + n);
-            size_t at_index = 0;
-            for (const Subspace &s : final_set) {
-                for (; at_index < s.lo; ++at_index) out.push_back(regs[at_index]);
-                std::vector<Flat> part(regs.begin() + s.lo, regs.begin() + s.hi);
-                std::vector<Flat> trial_part = part;
-                bool fits = true;
-                for (uint32_t k : s.tensors) {
-                    uint64_t off;
-                    if (!best_fit_flat(trial_part, sizes[k], kNewTag + k, off)) { fits = false; break; }
-                    dst[k] = off;
-                }
-                if (fits) {
-                    part.swap(trial_part);
-                } else {
-                    // merge: slide every allocated region to the subspace's low end in
-                    // address order, then place the tensors in the free tail
-                    const uint64_t start = part.front().off;
-                    const uint64_t end = part.back().off + part.back().len;
-                    uint64_t at = start;
-                    std::vector<Flat> packed;
-                    for (const Flat &r : part) {
-                        if (r.free) continue;
-                        if (r.off != at) {
-                            const Entry &e = entries_.at(r.tag);
-                            plan.moves.push_back(Move{e.id, r.off, at, e.nbytes, e.fp});
-                            plan.moved_bytes += e.nbytes;
-                        }
-                        packed.push_back(Flat{at, r.len, false, r.tag});
-                        at += r.len;
-                    }
-                    for (uint32_t k : s.tensors) {
-                        dst[k] = at;
-                        packed.push_back(Flat{at, sizes[k], false, kNewTag + k});
-                        at += sizes[k];
-                    }
-                    if (at > end) return ERR_NOSPACE;      // cannot happen: packing respects free bytes
-                    if (at < end) packed.push_back(Flat{at, end - at, true, 0});
-                    part.swap(packed);
-                }
-                out.insert(out.end(), part.begin(), part.end());
-                at_index = s.hi;
+            const Packer packer(regs, sizes, (flags & PLAN_PACK_TEXT) != 0, (flags & PLAN_CAP_TEXT) != 0);
+            std::vector<Packer::Piece> start;
+            if (!packer.deal(order, movable, start)) return ERR_NOSPACE;
+            const std::vector<Packer::Piece> pieces = packer.run(std::move(start));
+            for (const Packer::Piece &pc : pieces) {
+                // only residents inside a piece that takes tensors can ever move
+                plan.merge_bound += packer.used_bytes(pc.lo, pc.hi);
+                uint64_t need = 0;
+                for (uint32_t k : pc.tensors) need += sizes[k];
+                // cannot happen by free bytes; the text's capacity counts allocated bytes as room
+                if (need > packer.free_bytes(pc.lo, pc.hi)) return ERR_NOSPACE;
             }
-            for (; at_index < regs.size(); ++at_index) out.push_back(regs[at_index]);
-            work.rebuild(out);
+            for (const Packer::Piece &pc : pieces) {
+                const uint64_t begin = regs[pc.lo].off, end = regs[pc.hi - 1].off + regs[pc.hi - 1].len;
+                // best fit restricted to the piece: its holes by (length, offset)
+                std::set<std::pair<uint64_t, uint64_t>> holes;
+                for (size_t i = pc.lo; i < pc.hi; ++i)
+                    if (regs[i].free) holes.insert({regs[i].len, regs[i].off});
+                std::vector<std::pair<uint32_t, uint64_t>> placed;
+                for (uint32_t k : pc.tensors) {
+                    auto h = holes.lower_bound({sizes[k], 0});
+                    if (h == holes.end()) break;
+                    const uint64_t len = h->first, off = h->second;
+                    holes.erase(h);
+                    if (len > sizes[k]) holes.insert({len - sizes[k], off + sizes[k]});
+                    placed.push_back({k, off});
+                }
+                if (placed.size() == pc.tensors.size()) {
+                    for (const auto &kd : placed) {               // same order, so each hole is carved the same way
+                        work.take(kd.second, sizes[kd.first], kNewTag + kd.first);
+                        dst[kd.first] = kd.second;
+                    }
+                    continue;
+                }
+                // merge: the residents slide to the piece's low end in address order, the
+                // tensors follow, what is left is one free region
+                std::vector<Flat> packed;
+                uint64_t at = begin;
+                for (size_t i = pc.lo; i < pc.hi; ++i) {
+                    if (regs[i].free) continue;
+                    if (regs[i].off != at) {
+                        const Entry &e = entries_.at(regs[i].tag);
+                        plan.moves.push_back(Move{e.id, regs[i].off, at, e.nbytes, e.fp});
+                        plan.moved_bytes += e.nbytes;
+                    }
+                    packed.push_back(Flat{at, regs[i].len, false, regs[i].tag});
+                    at += regs[i].len;
+                }
+                for (uint32_t k : pc.tensors) {
+                    dst[k] = at;
+                    packed.push_back(Flat{at, sizes[k], false, kNewTag + k});
+                    at += sizes[k];
+                }
+                if (at > end) return ERR_NOSPACE;                 // ruled out by the check above
+                if (at < end) packed.push_back(Flat{at, end - at, true, 0});
+                work.splice(begin, end, packed);
+            }
         }
     }
 

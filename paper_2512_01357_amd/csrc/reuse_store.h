@@ -22,7 +22,9 @@ enum Status : int32_t {
     ERR_NOMEM = -6, ERR_CORRUPT = -7
 };
 
-enum PlanFlags : uint32_t { PLAN_CONFIRM = 1, PLAN_EVICT = 2, PLAN_MERGE = 4, PLAN_ALIAS = 8, PLAN_PACK_TEXT = 16 };
+enum PlanFlags : uint32_t {
+    PLAN_CONFIRM = 1, PLAN_EVICT = 2, PLAN_MERGE = 4, PLAN_ALIAS = 8, PLAN_PACK_TEXT = 16, PLAN_CAP_TEXT = 32
+};
 
 // Region tags: 0 = none, otherwise an entry id; ids at or above kNewTag mark
 // the slot of tensor (tag - kNewTag) of a plan that has not been committed.
@@ -72,7 +74,7 @@ public:
 
     struct Flat { uint64_t off, len; bool free; uint64_t tag; };
     std::vector<Flat> flatten() const;
-    void rebuild(const std::vector<Flat> &flat);
+    void splice(uint64_t start, uint64_t end, const std::vector<Flat> &flats);
 
 private:
     std::map<uint64_t, Region> by_off_;
@@ -174,8 +176,5 @@ private:
     std::unordered_map<uint64_t, Model> models_;
     std::unordered_map<uint64_t, ModelCost> costs_;
 };
-
-// ---- Algorithm 1 on a flat Region List (exposed for the planner only)
-struct Subspace { size_t lo, hi; std::vector<uint32_t> tensors; };   // regions [lo, hi), tensor subset
 
 }  // namespace tg

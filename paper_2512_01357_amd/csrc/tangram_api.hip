@@ -23,8 +23,9 @@ using tgk::u64;
 
 // Loads in flight per lane (U) and resident workgroups per compute unit for
 // each kernel, the size up to which a missing tensor rides in the gather launch,
-// and the copy-grouping threshold (0: none).  Chosen by measurement on MI355X.
-constexpr tg_tuning kDefaultTuning = {8, 4, 4, 1, 4, 2, uint64_t(64) << 10, 0};
+// the copy-grouping threshold (0: none), and whether a verifying load fingerprints
+// copied tensors inside the copy launch.  Chosen by measurement on MI355X.
+constexpr tg_tuning kDefaultTuning = {8, 4, 4, 1, 4, 2, uint64_t(64) << 10, 0, 1, 0};
 
 // A move whose source and destination overlap goes through this much staging at a time.
 constexpr size_t kBounceBytes = size_t(128) << 20;
@@ -137,6 +138,8 @@ struct tg_load_plan {
 namespace {
 
 size_t align_up(size_t n, size_t a) { return (n + a - 1) / a * a; }
+
+tgk::Copy copy_row(u64 dst, u64 src, u64 nbytes) { return tgk::Copy{dst, src, nbytes, 0, 0, 0}; }
 
 // Layout of one launch's table inside the scratch buffers.
 struct TableLayout {
@@ -365,7 +368,7 @@ tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
                 uint64_t len = std::min<uint64_t>(left, src0 - d);
                 if (len < left) len &= ~uint64_t(15);
                 if (len == 0) break;
-                in.push_back(tgk::Copy{base + d, base + s, len});
+                in.push_back(copy_row(base + d, base + s, len));
                 traffic += 2 * len;
                 done += len;
                 if (done < m.nbytes) break;                 // cut short: the launch is full
@@ -381,8 +384,8 @@ tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
                 uint64_t len = std::min<uint64_t>(left, kBounceBytes - staged);
                 if (len < left) len &= ~uint64_t(15);
                 if (len == 0) break;
-                in.push_back(tgk::Copy{bounce + staged, base + s, len});
-                out.push_back(tgk::Copy{base + d, bounce + staged, len});
+                in.push_back(copy_row(bounce + staged, base + s, len));
+                out.push_back(copy_row(base + d, bounce + staged, len));
                 staged += (len + 15) & ~uint64_t(15);
                 traffic += 4 * len;
                 done += len;
@@ -539,7 +542,7 @@ namespace {
 
 struct FeedItem { u32 k; const char *src; };            // tensor index, host address of its bytes
 struct FpLaunch { size_t desc_off = 0, prefix_off = 0, result_off = 0; u32 n = 0, tiles = 0; u64 bytes = 0; };
-struct CopyLaunch { size_t desc_off = 0, prefix_off = 0, ticket_off = 0; u32 n = 0, tiles = 0; };
+struct CopyLaunch { size_t desc_off = 0, prefix_off = 0, ticket_off = 0; u32 n = 0, tiles = 0; bool fused = false; };
 
 char *tab_h(Session &s) { return static_cast<char *>(s.pool->dev.h); }
 char *tab_d(Session &s) { return static_cast<char *>(s.pool->dev.d); }
@@ -586,10 +589,31 @@ tg_status launch_copy(Session &s, const CopyLaunch &c) {
     const u32 U = pick_u(tune.gather_unroll);
     char *d = tab_d(s);
     const u32 grid = grid_for(s.pool->dev.cu_count, c.tiles, tune.gather_wgs_per_cu);
-    TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU><<<dim3(grid), dim3(tgk::kCopyThreads), 0, s.sg>>>(
-                    reinterpret_cast<const tgk::Copy *>(d + c.desc_off),
-                    reinterpret_cast<const u32 *>(d + c.prefix_off), c.n, reinterpret_cast<u32 *>(d + c.ticket_off)));
+    const tgk::Copy *rows = reinterpret_cast<const tgk::Copy *>(d + c.desc_off);
+    const u32 *prefix = reinterpret_cast<const u32 *>(d + c.prefix_off);
+    u32 *ticket = reinterpret_cast<u32 *>(d + c.ticket_off);
+    if (c.fused) {
+        u64 *out = reinterpret_cast<u64 *>(d + s.results_off);
+        TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU, true><<<dim3(grid), dim3(tgk::kCopyThreads), 0, s.sg>>>(
+                        rows, prefix, c.n, ticket, out));
+    } else {
+        TG_FOR_U(U, tgk::gather_kernel<tgk::kCopyThreads, kU, false><<<dim3(grid), dim3(tgk::kCopyThreads), 0, s.sg>>>(
+                        rows, prefix, c.n, ticket, nullptr));
+    }
     TG_HIP(hipGetLastError());
+    return TG_OK;
+}
+
+// Makes a copy launch fingerprint what it copies: row i's sum goes to a result word of its own,
+// remembered as tensor ops[i]'s.
+tg_status fuse_fingerprints(Session &s, std::vector<tgk::Copy> &rows, const std::vector<u32> &ops) {
+    if (s.results_used + rows.size() > s.results_cap) return TG_ERR_NOMEM;
+    for (size_t i = 0; i < rows.size(); ++i) {
+        rows[i].slot = s.results_used++;
+        rows[i].word0 = 0;
+        s.result_ref.push_back(int64_t(ops[i]));
+        s.t.fused_verify_bytes += rows[i].nbytes;
+    }
     return TG_OK;
 }
 
@@ -801,7 +825,7 @@ void split_small(const Session &s, const std::vector<FeedItem> &items, const voi
         const tg::Op &op = pl.ops[it.k];
         const u64 mapped = u64(uintptr_t(host_dev)) + u64(it.src - static_cast<const char *>(host_base));
         if (host_dev && small > 0 && op.nbytes <= small && (mapped & 15u) == 0) {
-            small_rows.push_back(tgk::Copy{base + op.dst_off, mapped, op.nbytes});
+            small_rows.push_back(copy_row(base + op.dst_off, mapped, op.nbytes));
             small_ops.push_back(it.k);
         } else {
             dma.push_back(it);
@@ -868,20 +892,26 @@ tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_arg
     s.t = plan->timing;                                   // keeps what tg_plan measured
     s.t.gather_ms = s.t.h2d_ms = s.t.verify_ms = s.t.move_ms = 0.f;
     s.t.gather_bytes = s.t.h2d_bytes = s.t.verify_bytes = s.t.move_bytes = s.t.move_traffic_bytes = 0;
+    s.t.fused_verify_bytes = 0;
     s.t.h2d_copies = s.t.move_launches = s.t.verify_launches = s.t.feeds = 0;
 
     // ---- what the gather launch copies, and what is in place once it has run
     const size_t n = pl.ops.size();
     std::vector<tgk::Copy> copies;
-    std::vector<u32> group0;
+    std::vector<u32> copy_ops;                            // tensor of each row of `copies`
+    std::vector<u32> group0;                              // in place without a copy: hits of an aliasing plan
     std::vector<FeedItem> missing;
+    const bool fuse = verify && pool->tune.fuse_verify != 0;
     try {
         s.fed.assign(n, 1);
         for (size_t k = 0; k < n; ++k) {
             const tg::Op &op = pl.ops[k];
             if (op.kind == 0) {
-                group0.push_back(u32(k));
-                if (!pl.alias) copies.push_back(tgk::Copy{base + op.dst_off, base + op.src_off, op.nbytes});
+                if (pl.alias || !fuse) group0.push_back(u32(k));
+                if (!pl.alias) {
+                    copies.push_back(copy_row(base + op.dst_off, base + op.src_off, op.nbytes));
+                    copy_ops.push_back(u32(k));
+                }
             } else {
                 s.fed[k] = 0;
                 s.unfed += 1;
@@ -894,7 +924,8 @@ tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_arg
             std::vector<u32> small_ops;
             split_small(s, missing, pl.host_base, device_mapping(pl.host_base), copies, small_ops, *first_dma);
             for (u32 k : small_ops) {
-                group0.push_back(k);
+                copy_ops.push_back(k);
+                if (!fuse) group0.push_back(k);
                 s.fed[k] = 1;
                 s.unfed -= 1;
             }
@@ -907,8 +938,8 @@ tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_arg
     // ---- room for every table this load can need (the buffers cannot grow once a kernel reads them)
     // results; the gather's and the moves' tables; two span tables; per missing tensor one
     // feed at worst, each a dozen small tables padded to 256 bytes
-    size_t bound = 8192 + (n + pl.moves.size()) * 64 + copies.size() * 32 + (size_t(s.unfed) + first_dma_count(first_dma) + 1) * 4096;
-    for (const auto &rows : move_rows) bound += rows.size() * 32 + 1280;
+    size_t bound = 8192 + (n + pl.moves.size()) * 64 + copies.size() * 48 + (size_t(s.unfed) + first_dma_count(first_dma) + 1) * 4096;
+    for (const auto &rows : move_rows) bound += rows.size() * 48 + 1280;
     if ((rc = pool->dev.ensure(bound)) != TG_OK) return rc;
     s.cap = pool->dev.cap;
     if (verify) {
@@ -923,6 +954,10 @@ tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_arg
     try {
         for (size_t i = 0; i < move_rows.size(); ++i)
             if ((rc = place_copy_launch(s, move_rows[i], move_launch[i])) != TG_OK) return rc;
+        if (fuse && !copies.empty()) {
+            if ((rc = fuse_fingerprints(s, copies, copy_ops)) != TG_OK) return rc;
+            gather.fused = true;
+        }
         if (!copies.empty() && (rc = place_copy_launch(s, copies, gather)) != TG_OK) return rc;
         if (verify) {
             if ((rc = place_verify(s, group0, false, fp_group0)) != TG_OK) return rc;
@@ -995,14 +1030,19 @@ tg_status session_feed(Session &s, const void *seg_base, const std::vector<FeedI
     if (!small_rows.empty()) {
         CopyLaunch cl;
         FpLaunch fp;
+        const bool fuse = s.verify && s.pool->tune.fuse_verify != 0;
+        if (fuse) {
+            if ((rc = fuse_fingerprints(s, small_rows, small_ops)) != TG_OK) return rc;
+            cl.fused = true;
+        }
         if ((rc = place_copy_launch(s, small_rows, cl)) != TG_OK) return rc;
-        if (s.verify && (rc = place_verify(s, small_ops, false, fp)) != TG_OK) return rc;
+        if (s.verify && !fuse && (rc = place_verify(s, small_ops, false, fp)) != TG_OK) return rc;
         if ((rc = upload_tables(s)) != TG_OK) return rc;
         s.wrote = true;
         if ((rc = launch_copy(s, cl)) != TG_OK) return rc;
         if ((rc = new_event(s, &tk.kernel)) != TG_OK) return rc;
         TG_HIP(hipEventRecord(tk.kernel, s.sg));
-        if (s.verify && (rc = launch_verify(s, fp)) != TG_OK) return rc;
+        if (s.verify && !fuse && (rc = launch_verify(s, fp)) != TG_OK) return rc;
         for (const auto &c : small_rows) s.t.gather_bytes += c.nbytes;
     }
     if ((rc = feed_transfers(s, dma, may_block, &tk.transfer)) != TG_OK) return rc;
@@ -1281,7 +1321,7 @@ tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, vo
 tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
                   tg_load_plan **out) {
     if (!pool || !out) return TG_ERR_INVALID;
-    if (flags & ~(TG_PLAN_CONFIRM | TG_PLAN_EVICT | TG_PLAN_MERGE | TG_PLAN_ALIAS | TG_PLAN_PACK_TEXT))
+    if (flags & ~(TG_PLAN_CONFIRM | TG_PLAN_EVICT | TG_PLAN_MERGE | TG_PLAN_ALIAS | TG_PLAN_PACK_TEXT | TG_PLAN_CAP_TEXT))
         return TG_ERR_INVALID;
     const auto t0 = std::chrono::steady_clock::now();
     std::vector<tg::TensorIn> tensors;

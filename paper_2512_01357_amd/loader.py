@@ -258,10 +258,10 @@ class ReusePool:
         return RegisteredModel(model_id, host, offs, sizes, fps)
 
     @staticmethod
-    def _plan_flags(confirm=False, evict=False, merge=False, alias=False, pack_text=False) -> int:
+    def _plan_flags(confirm=False, evict=False, merge=False, alias=False, pack_text=False, cap_text=False) -> int:
         return ((tg.TG_PLAN_CONFIRM if confirm else 0) | (tg.TG_PLAN_EVICT if evict else 0)
                 | (tg.TG_PLAN_MERGE if merge else 0) | (tg.TG_PLAN_ALIAS if alias else 0)
-                | (tg.TG_PLAN_PACK_TEXT if pack_text else 0))
+                | (tg.TG_PLAN_PACK_TEXT if pack_text else 0) | (tg.TG_PLAN_CAP_TEXT if cap_text else 0))
 
     def _plan_info(self, plan, details: bool) -> dict:
         info = tg.tg_plan_info(plan)
@@ -278,11 +278,11 @@ class ReusePool:
 
     def load(self, model: RegisteredModel, confirm: bool = False, verify: bool = False,
              evict: bool = False, merge: bool = False, alias: bool = False,
-             pack_text: bool = False, details: bool = True) -> Tuple[List[int], dict]:
+             pack_text: bool = False, cap_text: bool = False, details: bool = True) -> Tuple[List[int], dict]:
         """tg_plan + tg_assemble.  Returns device addresses and what the plan held
         (with details=False only its totals: no per-tensor rows are fetched);
         info["timing"] is the plan's tg_timing."""
-        flags = self._plan_flags(confirm, evict, merge, alias, pack_text)
+        flags = self._plan_flags(confirm, evict, merge, alias, pack_text, cap_text)
         plan = tg.tg_plan(self.pool, model.desc, flags, self.stream_gather)
         try:
             info = self._plan_info(plan, details)
@@ -295,19 +295,23 @@ class ReusePool:
 
     def load_streamed(self, model: RegisteredModel, segments, verify: bool = False, evict: bool = False,
                       merge: bool = False, alias: bool = False, pack_text: bool = False,
-                      details: bool = True) -> Tuple[List[int], dict]:
+                      cap_text: bool = False, details: bool = True) -> Tuple[List[int], dict]:
         """A load whose missing tensors pass through a Model Cache smaller than
         the model: tg_plan (no host image needed), tg_assemble_begin, then one
         tg_assemble_feed per segment, then tg_assemble_wait.
 
         ``segments(missing)`` is a generator: given the indices of the tensors
         the plan transfers, it yields (pinned address, length, [(tensor index,
-        offset in the segment)]) each time its buffer holds the next piece; it is
-        resumed only after the device has read the previous piece.
+        offset in the segment)]) each time its buffer holds the next piece.  The
+        first piece is asked for before the load begins (the Model Cache holds it
+        when the model is switched in); the generator is resumed only after the
+        device has finished everything that the previous feed started, so that
+        whatever it does to refill its buffer never runs beside the load's own
+        kernels and copies.
         info["library_s"] is the time spent inside the library's calls and
         waiting for the device; the rest of the wall time is the generator
         refilling its buffer."""
-        flags = self._plan_flags(False, evict, merge, alias, pack_text)
+        flags = self._plan_flags(False, evict, merge, alias, pack_text, cap_text)
         t0 = time.perf_counter()
         plan = tg.tg_plan(self.pool, model.desc, flags, self.stream_gather)
         lib_s = time.perf_counter() - t0
@@ -317,16 +321,25 @@ class ReusePool:
             if not details:
                 for key in ("ops", "moves", "evictions"):
                     info.pop(key)
+            pieces = iter(segments(missing))
+            piece = next(pieces, None)                       # the cache's first piece: there before the load starts
+            torch.cuda.synchronize(self.device)
             t0 = time.perf_counter()
             tg.tg_assemble_begin(self.pool, plan, tg.TG_ASSEMBLE_VERIFY if verify else 0, **self._stream_args())
             lib_s += time.perf_counter() - t0
             n_feeds = 0
-            for ptr, nbytes, rows in segments(missing):
+            while piece is not None:
+                ptr, nbytes, rows = piece
                 t0 = time.perf_counter()
                 ticket = tg.tg_assemble_feed(self.pool, plan, ptr, nbytes, rows)
                 tg.tg_assemble_feed_wait(self.pool, plan, ticket)
-                lib_s += time.perf_counter() - t0
                 n_feeds += 1
+                lib_s += time.perf_counter() - t0
+                # the fingerprints of this piece finish before the refill of the next one starts
+                t0 = time.perf_counter()
+                self.stream_gather.synchronize()
+                lib_s += time.perf_counter() - t0
+                piece = next(pieces, None)
             t0 = time.perf_counter()
             ptrs = tg.tg_assemble_wait(self.pool, plan, model.desc.n)
             lib_s += time.perf_counter() - t0

@@ -26,6 +26,7 @@ TG_PLAN_EVICT = 2
 TG_PLAN_MERGE = 4
 TG_PLAN_ALIAS = 8
 TG_PLAN_PACK_TEXT = 16
+TG_PLAN_CAP_TEXT = 32
 TG_ASSEMBLE_VERIFY = 1
 TG_RELEASE_EVICT = 1
 TG_OP_REUSE = 0
@@ -95,14 +96,17 @@ class tg_timing(ctypes.Structure):
         "compare_ms", "gather_ms", "h2d_ms", "verify_ms", "plan_host_ms", "move_ms")]
         + [(n, ctypes.c_uint64) for n in ("compare_bytes", "gather_bytes", "h2d_bytes", "verify_bytes")]
         + [(n, ctypes.c_uint32) for n in ("h2d_copies", "move_launches", "verify_launches", "feeds")]
-        + [("move_bytes", ctypes.c_uint64), ("move_traffic_bytes", ctypes.c_uint64)])
+        + [("move_bytes", ctypes.c_uint64), ("move_traffic_bytes", ctypes.c_uint64),
+           ("fused_verify_bytes", ctypes.c_uint64)])
 
 
 class tg_tuning(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in (
         "fingerprint_unroll", "fingerprint_wgs_per_cu", "gather_unroll", "gather_wgs_per_cu",
         "compare_unroll", "compare_wgs_per_cu")] + [("h2d_kernel_max_bytes", ctypes.c_uint64),
-                                                     ("h2d_group_bytes", ctypes.c_uint64)]
+                                                     ("h2d_group_bytes", ctypes.c_uint64),
+                                                     ("fuse_verify", ctypes.c_uint32),
+                                                     ("reserved", ctypes.c_uint32)]
 
 
 class tg_feed_row(ctypes.Structure):

@@ -16,7 +16,7 @@ STRUCTS = ["tg_span", "tg_pair", "tg_tensor_desc", "tg_model_desc", "tg_plan_op"
            "tg_plan_summary", "tg_stats", "tg_timing", "tg_tuning", "tg_assemble_args", "tg_feed_row"]
 CONSTANTS = ["TG_OK", "TG_ERR_INVALID", "TG_ERR_NOSPACE", "TG_ERR_STALE", "TG_ERR_NOTFOUND", "TG_ERR_HIP",
              "TG_ERR_NOMEM", "TG_ERR_CORRUPT", "TG_PLAN_CONFIRM", "TG_PLAN_EVICT", "TG_PLAN_MERGE",
-             "TG_PLAN_ALIAS", "TG_PLAN_PACK_TEXT", "TG_ASSEMBLE_VERIFY", "TG_RELEASE_EVICT", "TG_OP_REUSE",
+             "TG_PLAN_ALIAS", "TG_PLAN_PACK_TEXT", "TG_PLAN_CAP_TEXT", "TG_ASSEMBLE_VERIFY", "TG_RELEASE_EVICT", "TG_OP_REUSE",
              "TG_OP_H2D", "TG_NOALLOC_MAX_SPANS"]
 
 

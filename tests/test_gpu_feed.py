@@ -151,7 +151,9 @@ def test_load_in_steps_through_a_small_segment_matches_the_oracle(seg_mib, verif
     b.check_image()
     assert t["feeds"] == feeds and (feeds >= 2 or seg_mib > 72)
     assert t["h2d_bytes"] + t["gather_bytes"] == sum(op.nbytes for op in oplan.ops)
-    assert (t["verify_bytes"] == sum(op.nbytes for op in oplan.ops)) == verify
+    # a verifying load fingerprints every tensor once: inside the copy launch or by a launch of its own
+    assert t["verify_bytes"] + t["fused_verify_bytes"] == (sum(op.nbytes for op in oplan.ops) if verify else 0)
+    assert (t["fused_verify_bytes"] > 0) == verify
     b.release(2, evict=True)
     b.check_image()
     seg.free()
@@ -357,3 +359,42 @@ def test_copy_grouping_threshold_changes_the_copies_not_the_result():
     # no limit: one copy; 2 MiB: a copy stops growing once it is past 2 MiB (3 + 3 + 2 tensors);
     # the paper's 8 MB: everything in one copy here; 1 byte: nothing is merged
     assert copies == {0: 1, 2 * mib: 3, 8 * mib: 1, 1: 8}
+
+
+@pytest.mark.parametrize("fuse", [1, 0])
+@pytest.mark.parametrize("unroll", [2, 4, 8, 16])
+def test_a_verifying_load_fingerprints_inside_the_copy_launch_or_after_it(fuse, unroll):
+    say("verify: fuse_verify=%d, gather_unroll=%d" % (fuse, unroll))
+    rnd = random.Random(40 + unroll)
+    b = Pair(256 << 20)
+    b.pool.set_tuning(fuse_verify=fuse, gather_unroll=unroll)
+    tile = 1024 * 16 * unroll
+    sizes = [1, 7, 16, 24, 255, 4096, 5000, 65536, 65537, tile - 16, tile - 8, tile, tile + 1, tile + 24, 2 * tile,
+             3 * tile + 4096 + 5, (1 << 20) + 24, 3 * (1 << 20) + 1, 9 << 20]
+    a = [rbytes(rnd, n) for n in sizes]
+    b.load_whole(1, a)
+    b.release(1)
+    m2 = [a[i] if i % 3 else rbytes(rnd, sizes[i]) for i in range(len(sizes))]
+    oplan = b.load_whole(2, m2)
+    t = b.pool.last_timing
+    through_copy_launch = sum(op.nbytes for op in oplan.ops if op.kind == 0 or op.nbytes <= 65536)
+    assert t["fused_verify_bytes"] == (through_copy_launch if fuse else 0)
+    assert t["verify_bytes"] + t["fused_verify_bytes"] == sum(sizes)
+    b.release(2, evict=True)
+    # a resident tensor is damaged in the pool; a verifying load that reuses it is refused either way
+    victim = next(e for e in b.store.entries if e.nbytes == sizes[-2])
+    b.pool.slab[victim.off + 12345] ^= 0x10
+    torch.cuda.synchronize()
+    host, offs = pack(m2)
+    arena = HostArena(host.size)
+    arena.numpy()[:] = host
+    reg = RegisteredModel(3, arena, offs, sizes, [r[1] for r in b.rows(m2, offs)])
+    with pytest.raises(tg.TgError) as e:
+        b.pool.load(reg, verify=True)
+    assert e.value.status == tg.TG_ERR_CORRUPT
+    b.pool.slab[victim.off + 12345] ^= 0x10
+    torch.cuda.synchronize()
+    b.check_image()                                   # nothing was committed
+    b.load_whole(3, m2)
+    arena.free()
+    b.close()

@@ -16,9 +16,10 @@ FAKE_HOST = 1 << 41
 U = 256
 
 
-def flags_of(evict=False, merge=False, alias=False, pack_text=False):
+def flags_of(evict=False, merge=False, alias=False, pack_text=False, cap_text=False):
     return (tg.TG_PLAN_EVICT if evict else 0) | (tg.TG_PLAN_MERGE if merge else 0) | \
-        (tg.TG_PLAN_ALIAS if alias else 0) | (tg.TG_PLAN_PACK_TEXT if pack_text else 0)
+        (tg.TG_PLAN_ALIAS if alias else 0) | (tg.TG_PLAN_PACK_TEXT if pack_text else 0) | \
+        (tg.TG_PLAN_CAP_TEXT if cap_text else 0)
 
 
 def plan_both(pool, store, mid, tensors, host_bytes, **fl):
@@ -188,7 +189,7 @@ def test_abandoned_plan_keeps_its_evictions_and_moves_only():
 def test_unknown_flag_bits_are_refused():
     pool = tg.tg_pool_create(FAKE_BASE, 4096, 256)
     with pytest.raises(tg.TgError) as e:
-        tg.tg_plan(pool, tg.ModelDesc(1, FAKE_HOST, 4096, [(512, 1, 0)]), 32)
+        tg.tg_plan(pool, tg.ModelDesc(1, FAKE_HOST, 4096, [(512, 1, 0)]), 64)
     assert e.value.status == tg.TG_ERR_INVALID
     tg.tg_pool_destroy(pool)
 
@@ -208,7 +209,7 @@ def history(seed):
             picks = [contents[rnd.randrange(30)] for _ in range(rnd.randrange(1, 8))]
             rows, hb = layout_rows([p[0] for p in picks], [p[1] for p in picks])
             fl = dict(evict=rnd.random() < 0.7, merge=rnd.random() < 0.7, alias=rnd.random() < 0.5,
-                      pack_text=rnd.random() < 0.5)
+                      pack_text=rnd.random() < 0.5, cap_text=rnd.random() < 0.3)
             mid = next_id
             if retained and rnd.random() < 0.25:
                 mid = rnd.choice(retained)
