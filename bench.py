@@ -74,10 +74,12 @@ def profiled_alu_rate():
     return None, None
 
 
-def kernel_shapes(tuning):
+def kernel_shapes(tuning, verify):
+    """Template arguments x workgroups per compute unit of the two kernels a load launches."""
     u = lambda v: 16 if v >= 16 else 8 if v >= 8 else 4 if v >= 4 else 2      # noqa: E731
+    fused = "true" if (verify and tuning["fuse_verify"]) else "false"
     return {"fingerprint": "fingerprint_kernel<256,%d>x%d" % (u(tuning["fingerprint_unroll"]), tuning["fingerprint_wgs_per_cu"]),
-            "gather": "gather_kernel<1024,%d>x%d" % (u(tuning["gather_unroll"]), tuning["gather_wgs_per_cu"])}
+            "gather": "gather_kernel<1024,%d,%s>x%d" % (u(tuning["gather_unroll"]), fused, tuning["gather_wgs_per_cu"])}
 
 
 # ------------------------------------------------------------------ pieces of a run
@@ -190,6 +192,17 @@ def cpu_baseline(runner, w, name):
     }
 
 
+def pmc_calibration_kernel(torch):
+    """One plain elementwise kernel of known traffic (reads 1 GiB, writes 1 GiB), so that a
+    rocprofv3 --pmc run has something to scale its FETCH_SIZE / WRITE_SIZE read-outs by."""
+    a = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda:0")
+    b = torch.empty_like(a)
+    torch.cuda.synchronize()
+    torch.mul(a, 1.0, out=b)
+    torch.cuda.synchronize()
+    del a, b
+
+
 def kernel_figures(recs, verify, tuning, workload_name, plain_load):
     """roofline objects of the fingerprint (verify launches of a step together) and the gather."""
     steps = len(recs)
@@ -204,7 +217,7 @@ def kernel_figures(recs, verify, tuning, workload_name, plain_load):
     g_bytes, g_ms = 2 * total("gather_bytes"), total("gather_ms")
     g_launches = sum(1 for rec in recs if rec["timing"]["gather_ms"] > 0)
     fp_rate, g_rate = gbps(fp_bytes, fp_ms), gbps(g_bytes, g_ms)
-    shapes = kernel_shapes(tuning)
+    shapes = kernel_shapes(tuning, verify)
     kernels = {
         "fingerprint": {"bound": "hbm", "achieved": round(fp_rate, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                         "frac": round(fp_rate / HBM_PEAK_GBPS, 4),
@@ -219,6 +232,12 @@ def kernel_figures(recs, verify, tuning, workload_name, plain_load):
                    "algorithmic_bytes_per_launch": int(g_bytes / g_launches) if g_launches else 0,
                    "algorithmic_bytes_per_step": int(g_bytes / steps), "shape": shapes["gather"]},
     }
+    # a launch over a few megabytes is bound by its launch, not by HBM: no bandwidth claim is made for it
+    for k in kernels:
+        if 0 < kernels[k]["algorithmic_bytes_per_launch"] < (256 << 20):
+            kernels[k]["launch_bound_GBps"] = kernels[k]["achieved"]
+            kernels[k]["achieved"] = kernels[k]["frac"] = None
+            kernels[k]["note"] = "launches of under 256 MiB: bound by launch latency, not a bandwidth figure"
     # HBM traffic per step from rocprofv3 counters: only a tracked summary of this workload in this
     # launch shape counts; anything else is reported as not measured
     for k in kernels:
@@ -231,13 +250,16 @@ def kernel_figures(recs, verify, tuning, workload_name, plain_load):
     # integer-ALU co-limit of the fingerprint: what the mix alone (no loads) sustains on this chip
     rate, source = profiled_alu_rate()
     if rate:
+        # the gather launch of a verifying load does the same arithmetic on the bytes it copies
         kernels["fingerprint"]["alu_colimit"] = {"equivalent_GBps": round(rate * 8 / 1e9, 1),
                                                  "frac": round(fp_rate / (rate * 8 / 1e9), 4), "source": source}
+    fused = sum(rec["timing"]["fused_verify_bytes"] for rec in recs)
+    kernels["gather"]["fingerprinted_bytes_per_step"] = int(fused / steps)
     return kernels
 
 
 def dominant_roofline(kernels):
-    name = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    name = max(kernels, key=lambda k: kernels[k]["ms_per_step"] if kernels[k]["achieved"] is not None else -1.0)
     roofline = dict(kernels[name])
     roofline["kernel"] = name
     return roofline
@@ -276,12 +298,7 @@ def bench_resident(args, torch, w, link_peak, steps, warmup, with_extras, with_c
         % ("two streams" if r.pool.stream_h2d_second is not None else "one stream", SECOND_H2D_MEASUREMENT.get("cuda:0")))
 
     if args.pmc_calibration:
-        a = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda:0")
-        b = torch.empty_like(a)
-        torch.cuda.synchronize()
-        torch.mul(a, 1.0, out=b)          # an elementwise kernel: reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del a, b
+        pmc_calibration_kernel(torch)
 
     verify = not args.no_verify
     names = w.loads
@@ -345,7 +362,7 @@ def bench_resident(args, torch, w, link_peak, steps, warmup, with_extras, with_c
                    "plan_flags": sorted(k for k, v in w.load_flags.items() if v),
                    "h2d_streams": 2 if r.pool.stream_h2d_second is not None else 1,
                    "model_cache": "whole model pinned"},
-        "fingerprint_GBps": kernels["fingerprint"]["achieved"],
+        "fingerprint_GBps": kernels["fingerprint"]["achieved"] or kernels["fingerprint"].get("launch_bound_GBps"),
         "roofline": dominant_roofline(kernels),
         "kernels": kernels,
         "host_link": host_link_figures(recs, link_peak),
@@ -478,6 +495,8 @@ def bench_llama70b(args, torch, link_peak, levels, steps, warmup):
     st0 = r.pool.stats()
     tuning = tg.tg_pool_get_tuning(r.pool.pool)
     verify = not args.no_verify
+    if args.pmc_calibration:
+        pmc_calibration_kernel(torch)
     legs = []
     for name in w.loads:
         r.materialise(name)
@@ -519,7 +538,24 @@ def bench_llama70b(args, torch, link_peak, levels, steps, warmup):
             "plan_host_ms": round(sum(rec["timing"]["plan_host_ms"] for rec in recs) / steps, 4),
             "load_time_bound_ms": bound_ms(recs, link_peak),
         }
-        log("leg %s: %.1f GB/s, %.1f ms per load (bound %.1f), fingerprint %.0f GB/s, gather %.0f GB/s, link %.2f of %.2f GB/s"
+        if name == w.loads[0]:
+            # the fingerprint kernel on its own, launched back to back over the loaded model's slots
+            ptrs, _info = r.load(name, details=False)
+            reg = r.models[name]
+            spans = list(zip(ptrs, reg.sizes))
+            ms = []
+            for _ in range(6):
+                got, t_ms = tg.tg_fingerprint_ex(spans, r.pool.stream_gather, tuning=tuning, timed=True)
+                ms.append(t_ms)
+            if got != reg.fps:
+                raise RuntimeError("fingerprints of the loaded model differ from its descriptors")
+            r.release(name, True)
+            best = min(ms[1:])
+            leg["fingerprint_back_to_back"] = {
+                "GBps": round(reg.nbytes / (best * 1e-3) / 1e9, 1),
+                "frac": round(reg.nbytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "ms": round(best, 4),
+                "bytes": reg.nbytes, "launches": len(ms), "first_launch_GBps": round(reg.nbytes / (ms[0] * 1e-3) / 1e9, 1)}
+        log("leg %s: %.1f GB/s, %.1f ms per load (bound %.1f), fingerprint %s GB/s, gather %s GB/s, link %.2f of %.2f GB/s"
             % (leg["config"]["workload"], leg["value"], leg["ms_per_step"], leg["load_time_bound_ms"],
                kernels["fingerprint"]["achieved"], kernels["gather"]["achieved"], leg["host_link"]["achieved"], link_peak))
         legs.append(leg)

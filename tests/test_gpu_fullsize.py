@@ -42,7 +42,8 @@ def test_neox_20b_into_a_pool_that_is_too_small_full_size():
     plans, _ = run_workload_both(w)
     p = plans["M20"]
     assert len(p.evictions) > 1000 and p.evicted_bytes > 16e9
-    assert p.moves and p.moved_bytes < p.merge_bound
+    # the bound is what lies inside the subspaces that take tensors: a fraction of the 59 GB resident
+    assert p.moves and p.moved_bytes <= p.merge_bound < 10e9
     assert p.alias and 12.3e9 < p.reused_bytes < 12.5e9
     assert p.reused_bytes + p.transfer_bytes == w.models["M20"].nbytes
 
