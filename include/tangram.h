@@ -483,9 +483,10 @@ tg_status tg_assemble_ex(tg_pool *pool, tg_load_plan *plan, const tg_assemble_ar
                          void **out_dev_ptrs);
 
 /*
- * The same load in steps that do not block.  (Section 3.1: tensors that are
- * not found are loaded from the CPU-side Model Cache or the Model Store;
- * Section 3.4, Eq. 3: Store-to-Cache and Cache-to-GPU transfers overlap.)
+ * The same load in steps that do not block.  (Section 3.1 has two sources
+ * for what the Tensor Mapping does not hold, a cache in CPU memory and the
+ * storage behind it; Section 3.4, Eq. 3: filling the cache and emptying it
+ * into the GPU go on at the same time.)
  *
  * tg_assemble_async  enqueues everything tg_assemble_ex does -- moves, the
  *     gather, every host-to-device copy from the plan's host image, the

@@ -555,8 +555,9 @@ class ReuseStoreOracle:
     # ---------------------------------------------------------------- release
     def release(self, model_id: int, evict: bool = False) -> None:
         """The model instance ends.  Without ``evict`` its tensors stay
-        resident and matchable but no longer count as in use (the paper's
-        "inactive but resident" state, Section 3.1); with it the model gives
+        resident and matchable but no longer count as in use (Section 3.1:
+        a model that has stopped running keeps its tensors in the pool until
+        they are evicted); with it the model gives
         up its tensors, and those no other model owns are freed, their regions
         merged with free neighbours."""
         if model_id not in self.models:

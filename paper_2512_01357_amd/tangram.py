@@ -367,10 +367,14 @@ def tg_plan_ops(plan) -> Tuple[List[Tuple[int, int, int, int]], int, int]:
     return rows, int(reused.value), int(transfer.value)
 
 
+_SUMMARY_FIELDS = tuple(n for n, _ in tg_plan_summary._fields_)
+_TIMING_FIELDS = tuple(n for n, _ in tg_timing._fields_)
+
+
 def tg_plan_info(plan) -> dict:
     out = tg_plan_summary()
     _check(lib().tg_plan_info(plan, ctypes.byref(out)), "tg_plan_info")
-    return {n: int(getattr(out, n)) for n, _ in tg_plan_summary._fields_}
+    return {n: getattr(out, n) for n in _SUMMARY_FIELDS}
 
 
 def tg_plan_moves(plan) -> List[Tuple[int, int, int]]:
@@ -509,7 +513,7 @@ def tg_pool_set_profiling(pool, on: bool) -> None:
 def tg_plan_timing(plan) -> dict:
     t = tg_timing()
     _check(lib().tg_plan_timing(plan, ctypes.byref(t)), "tg_plan_timing")
-    return {n: getattr(t, n) for n, _ in tg_timing._fields_}
+    return {n: getattr(t, n) for n in _TIMING_FIELDS}
 
 
 def tg_host_alloc(nbytes: int) -> int:
