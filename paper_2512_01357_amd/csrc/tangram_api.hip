@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cstring>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -1129,7 +1130,7 @@ tg_status session_wait(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
 
 extern "C" {
 
-tg_status tg_pool_create(void *dev_base, uint64_t capacity, uint32_t align, tg_pool **out) {
+tg_status tg_pool_create(void *dev_base, uint64_t capacity, uint32_t align, tg_pool **out) try {
     if (!dev_base || !out || capacity == 0) return TG_ERR_INVALID;
     if (align < 16 || (align & (align - 1)) != 0) return TG_ERR_INVALID;
     const uint64_t base = uint64_t(reinterpret_cast<uintptr_t>(dev_base));
@@ -1139,6 +1140,8 @@ tg_status tg_pool_create(void *dev_base, uint64_t capacity, uint32_t align, tg_p
     if (!p) return TG_ERR_NOMEM;
     *out = p;
     return TG_OK;
+} catch (...) {
+    return TG_ERR_NOMEM;                          // a container could not grow
 }
 
 tg_status tg_pool_destroy(tg_pool *pool) {
@@ -1175,7 +1178,7 @@ tg_status tg_pool_regions(const tg_pool *pool, tg_region *out, uint32_t cap, uin
     return TG_OK;
 }
 
-tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint32_t *n) {
+tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint32_t *n) try {
     if (!pool || !n || (cap > 0 && !out)) return TG_ERR_INVALID;
     const std::vector<const tg::Entry *> rows = pool->store.entries_by_offset();
     for (size_t i = 0; i < rows.size() && i < cap; ++i)
@@ -1183,6 +1186,8 @@ tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint
                           rows[i]->active_refs};
     *n = uint32_t(rows.size());
     return TG_OK;
+} catch (...) {
+    return TG_ERR_NOMEM;                          // a container could not grow
 }
 
 tg_status tg_default_tuning(tg_tuning *out) {
@@ -1318,8 +1323,20 @@ tg_status tg_compare(const tg_pair *pairs, uint32_t n, uint32_t *out_differs, vo
     return tg_compare_ex(pairs, n, out_differs, stream, nullptr, nullptr);
 }
 
+static tg_status plan_impl(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
+                           tg_load_plan **out);
+
 tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
                   tg_load_plan **out) {
+    try {
+        return plan_impl(pool, model, flags, stream, out);
+    } catch (...) {                               // a container could not grow; nothing was changed
+        return TG_ERR_NOMEM;
+    }
+}
+
+static tg_status plan_impl(tg_pool *pool, const tg_model_desc *model, uint32_t flags, void *stream,
+                           tg_load_plan **out) {
     if (!pool || !out) return TG_ERR_INVALID;
     if (flags & ~(TG_PLAN_CONFIRM | TG_PLAN_EVICT | TG_PLAN_MERGE | TG_PLAN_ALIAS | TG_PLAN_PACK_TEXT | TG_PLAN_CAP_TEXT))
         return TG_ERR_INVALID;
@@ -1373,14 +1390,15 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
         }
     }
 
-    tg_load_plan *lp = new (std::nothrow) tg_load_plan();
+    std::unique_ptr<tg_load_plan> owner(new (std::nothrow) tg_load_plan());
+    tg_load_plan *lp = owner.get();
     if (!lp) return TG_ERR_NOMEM;
     lp->pool = pool;
     lp->plan.model_id = model->model_id;
     lp->plan.host_base = model->host_base;
     lp->plan.host_bytes = model->host_bytes;
     const tg::Status ps = store.plan(tensors, hits, flags, lp->plan);
-    if (ps != tg::OK) { delete lp; return tg_status(ps); }
+    if (ps != tg::OK) return tg_status(ps);
     lp->rows.resize(n);
     for (size_t k = 0; k < n; ++k) {
         const tg::Op &op = lp->plan.ops[k];
@@ -1394,7 +1412,7 @@ tg_status tg_plan(tg_pool *pool, const tg_model_desc *model, uint32_t flags, voi
     lp->timing.compare_ms = compare_ms;
     lp->timing.compare_bytes = compare_bytes;
     lp->timing.plan_host_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
-    *out = lp;
+    *out = owner.release();
     return TG_OK;
 }
 
@@ -1453,7 +1471,7 @@ void tg_plan_free(tg_load_plan *plan) {
     delete plan;
 }
 
-tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
+tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) try {
     if (!pool || !plan || pool->in_flight) return TG_ERR_INVALID;
     std::vector<uint64_t> dst;
     const tg::Status s = pool->store.commit(plan->plan, dst);
@@ -1462,15 +1480,23 @@ tg_status tg_commit(tg_pool *pool, tg_load_plan *plan, void **out_dev_ptrs) {
         for (size_t k = 0; k < dst.size(); ++k)
             out_dev_ptrs[k] = reinterpret_cast<void *>(uintptr_t(pool->store.base() + dst[k]));
     return TG_OK;
+} catch (...) {
+    return TG_ERR_NOMEM;                          // a container could not grow
 }
 
-tg_status tg_abandon(tg_pool *pool, tg_load_plan *plan) {
+tg_status tg_abandon(tg_pool *pool, tg_load_plan *plan) try {
     if (!pool || !plan || pool->in_flight) return TG_ERR_INVALID;
     return tg_status(pool->store.abandon(plan->plan));
+} catch (...) {
+    return TG_ERR_NOMEM;                          // a container could not grow
 }
 
 tg_status tg_assemble_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args) {
-    return session_begin(pool, plan, args, false, nullptr);
+    try {
+        return session_begin(pool, plan, args, false, nullptr);
+    } catch (...) {                               // a container could not grow
+        return plan && plan->session ? session_fail(plan, TG_ERR_NOMEM) : TG_ERR_NOMEM;
+    }
 }
 
 // Starts a load from the plan's whole host image.  may_block: the caller is
@@ -1487,7 +1513,11 @@ static tg_status begin_from_image(tg_pool *pool, tg_load_plan *plan, const tg_as
 }
 
 tg_status tg_assemble_async(tg_pool *pool, tg_load_plan *plan, const tg_assemble_args *args) {
-    return begin_from_image(pool, plan, args, false);
+    try {
+        return begin_from_image(pool, plan, args, false);
+    } catch (...) {
+        return plan && plan->session ? session_fail(plan, TG_ERR_NOMEM) : TG_ERR_NOMEM;
+    }
 }
 
 tg_status tg_assemble_feed(tg_pool *pool, tg_load_plan *plan, const void *seg_base, uint64_t seg_bytes,
@@ -1566,18 +1596,22 @@ tg_status tg_assemble(tg_pool *pool, tg_load_plan *plan, uint32_t flags, void *s
     return tg_assemble_ex(pool, plan, &args, out_dev_ptrs);
 }
 
-tg_status tg_release(tg_pool *pool, uint64_t model_id, uint32_t flags) {
+tg_status tg_release(tg_pool *pool, uint64_t model_id, uint32_t flags) try {
     if (!pool || pool->in_flight) return TG_ERR_INVALID;
     return tg_status(pool->store.release(model_id, (flags & TG_RELEASE_EVICT) != 0));
+} catch (...) {
+    return TG_ERR_NOMEM;                          // a container could not grow
 }
 
-tg_status tg_set_model_cost(tg_pool *pool, uint64_t model_id, double miss_prob, double load_bw, double alpha) {
+tg_status tg_set_model_cost(tg_pool *pool, uint64_t model_id, double miss_prob, double load_bw, double alpha) try {
     if (!pool) return TG_ERR_INVALID;
     return tg_status(pool->store.set_model_cost(model_id, miss_prob, load_bw, alpha));
+} catch (...) {
+    return TG_ERR_NOMEM;                          // a container could not grow
 }
 
 tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double link_bytes_per_s,
-                        uint64_t *reuse_bytes, double *est_load_s) {
+                        uint64_t *reuse_bytes, double *est_load_s) try {
     if (!pool || !reuse_bytes) return TG_ERR_INVALID;
     std::vector<tg::TensorIn> tensors;
     const tg_status rc = check_model(model, tensors);
@@ -1590,6 +1624,8 @@ tg_status tg_reuse_size(const tg_pool *pool, const tg_model_desc *model, double 
     // Eq. 3: t_load = (S - S') / B
     if (est_load_s) *est_load_s = double(total - reuse) / link_bytes_per_s;
     return TG_OK;
+} catch (...) {
+    return TG_ERR_NOMEM;                          // a container could not grow
 }
 
 tg_status tg_host_alloc(uint64_t nbytes, void **out) {
