@@ -43,7 +43,9 @@ class Both:
         self.store = ReuseStoreOracle(capacity, align)
         self.keep = []
 
-    def load(self, mid, tensors, **fl):
+    def load(self, mid, tensors, in_steps=0, **fl):
+        """Loads on both sides.  in_steps > 0: the library plans without a host image and is fed
+        the missing tensors in that many pieces (tg_assemble_begin / _feed / _wait)."""
         host, offs = pack(tensors, max(self.align, 16))
         arena = HostArena(host.size)
         arena.numpy()[:] = host
@@ -60,7 +62,17 @@ class Both:
                 self.pool.load(reg, **fl)
             assert e.value.status == tg.TG_ERR_NOSPACE
             return None, None
-        ptrs, info = self.pool.load(reg, verify=True, **fl)
+        if in_steps:
+            from paper_2512_01357_amd.loader import RegisteredModel
+            bare = RegisteredModel(mid, None, offs, sizes, want)
+
+            def pieces(missing):
+                n = max(1, -(-len(missing) // in_steps))
+                for i in range(0, len(missing), n):
+                    yield arena.ptr, arena.nbytes, [(k, offs[k]) for k in missing[i:i + n]]
+            ptrs, info = self.pool.load_streamed(bare, pieces, verify=True, **fl)
+        else:
+            ptrs, info = self.pool.load(reg, verify=True, **fl)
         assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops]
         assert info["moves"] == [(old, new, e.nbytes) for e, old, new in oplan.moves]
         assert info["evictions"] == [e.off for e in oplan.evictions]
@@ -288,7 +300,7 @@ def test_random_histories_with_every_flag_real_bytes(seed):
             mid = next_id
             if retained and rnd.random() < 0.25:
                 mid = rnd.choice(retained)
-            plan, dsts = b.load(mid, tensors, **fl)
+            plan, dsts = b.load(mid, tensors, in_steps=rnd.choice([0, 0, 1, 3]), **fl)
             if plan is None:
                 continue
             running[mid] = (tensors, dsts)
