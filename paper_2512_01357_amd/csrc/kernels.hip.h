@@ -291,10 +291,13 @@ __global__ __launch_bounds__(T) void compare_kernel(const Pair *__restrict__ pai
 // bytes that were read).  A tile's arithmetic is put off by one turn of the
 // loop: it runs right after the loads of the next tile have been issued, so the
 // integer units work while those loads and the previous stores are in flight
-// instead of holding up the next loads.  The wave sums meet in LDS and lane 0
-// adds them up when it draws the next ticket: the loop has one single place
-// where one lane works alone, which keeps every barrier in control flow that
-// the whole workgroup walks in step.
+// instead of holding up the next loads.  The wave sums meet in LDS; at the top
+// of the next turn the first lane of the second wave adds them up while the
+// first lane of the first wave draws the ticket.  Both of these lone-lane
+// blocks stand together at the top of the loop, before its first barrier: with
+// one at the end of the loop body and one at its top the compiler threaded the
+// lane from the first straight into the second, across the back edge, and the
+// barriers were no longer reached by the whole workgroup in step.
 template <int T, int U, bool FP>
 __global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copies,
                                                     const u32 *__restrict__ prefix, u32 n_copies,
@@ -314,15 +317,13 @@ __global__ __launch_bounds__(T) void gather_kernel(const Copy *__restrict__ copi
     bool pending = false;
     u32 pending_slot = 0;
     for (;;) {
-        if (tid == 0) {
-            if (FP && pending) {
-                u64 sum = 0;
+        if (FP && pending && tid == 64) {          // the second wave adds up the sums while the first draws
+            u64 sum = 0;
 #pragma unroll
-                for (int i = 0; i < T / 64; ++i) sum += wave_part[i];
-                atomicAdd(&out[pending_slot], sum);
-            }
-            next_tile = atomicAdd(ticket, 1u);
+            for (int i = 0; i < T / 64; ++i) sum += wave_part[i];
+            atomicAdd(&out[pending_slot], sum);
         }
+        if (tid == 0) next_tile = atomicAdd(ticket, 1u);
         pending = false;
         __syncthreads();
         const u32 t = __builtin_amdgcn_readfirstlane(next_tile);

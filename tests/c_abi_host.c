@@ -61,9 +61,49 @@ int main(void) {
         args.flags = 8u;
         CHECK(tg_assemble_ex(pool, plan, &args, ptrs) == TG_ERR_INVALID);
         CHECK(tg_assemble_ex(NULL, plan, &args, ptrs) == TG_ERR_INVALID);
+        /* the load in steps: none of its calls does anything to a plan whose load has not begun */
+        {
+            tg_feed_row row = {1, 0, 0};
+            uint32_t ticket = 99;
+            CHECK(tg_assemble_begin(pool, plan, NULL) == TG_ERR_INVALID);
+            CHECK(tg_assemble_async(pool, NULL, &args) == TG_ERR_INVALID);
+            CHECK(tg_assemble_feed(pool, plan, host, 4096, &row, 1, &ticket) == TG_ERR_INVALID && ticket == 99);
+            CHECK(tg_assemble_feed_wait(pool, plan, 0) == TG_ERR_INVALID);
+            CHECK(tg_assemble_wait(pool, plan, ptrs) == TG_ERR_INVALID);
+        }
     }
-    CHECK(tg_commit(pool, plan, ptrs) == TG_OK && ptrs[0] == base);
-    tg_plan_free(plan);
+    {   /* launch shape and profiling belong to the pool; the plan keeps its own timing */
+        tg_tuning def, cur;
+        tg_timing tm;
+        CHECK(tg_default_tuning(&def) == TG_OK && def.fingerprint_unroll == 8 && def.gather_unroll == 4);
+        CHECK(def.h2d_kernel_max_bytes == 65536 && def.h2d_group_bytes == 0 && def.fuse_verify == 1);
+        CHECK(tg_pool_get_tuning(pool, &cur) == TG_OK && memcmp(&cur, &def, sizeof def) == 0);
+        cur.gather_unroll = 8;
+        cur.h2d_group_bytes = 8u << 20;
+        CHECK(tg_pool_set_tuning(pool, &cur) == TG_OK);
+        CHECK(tg_pool_get_tuning(pool, &def) == TG_OK && def.gather_unroll == 8 && def.h2d_group_bytes == (8u << 20));
+        CHECK(tg_pool_set_tuning(pool, NULL) == TG_ERR_INVALID && tg_default_tuning(NULL) == TG_ERR_INVALID);
+        CHECK(tg_pool_set_profiling(pool, 1) == TG_OK && tg_pool_set_profiling(NULL, 1) == TG_ERR_INVALID);
+        CHECK(tg_plan_timing(plan, &tm) == TG_OK && tm.plan_host_ms > 0.0f && tm.gather_ms == 0.0f && tm.feeds == 0);
+        CHECK(tg_plan_timing(NULL, &tm) == TG_ERR_INVALID);
+    }
+    {   /* a model without a host image: rows only */
+        tg_load_plan *bare = NULL;
+        tg_tensor_desc d[1] = {{300, 0x5555, 123456789}};
+        tg_model_desc md = {9, NULL, 0, 1, 0, d};
+        tg_model_desc bad = {9, NULL, 64, 1, 0, d};
+        CHECK(tg_plan(pool, &md, 0, NULL, &bare) == TG_OK);
+        CHECK(tg_plan_ops(bare, &ops, &n, NULL, NULL) == TG_OK && n == 1 && ops[0].src_off == 123456789);
+        CHECK(tg_assemble(pool, bare, 0, NULL, NULL, NULL) == TG_ERR_INVALID);   /* nothing to copy from */
+        tg_plan_free(bare);
+        CHECK(tg_plan(pool, &bad, 0, NULL, &bare) == TG_ERR_INVALID);
+        CHECK(tg_plan(pool, &md, TG_PLAN_CONFIRM, NULL, &bare) == TG_ERR_INVALID);
+        CHECK(tg_plan_ops(plan, &ops, &n, NULL, NULL) == TG_OK);
+    }
+    {
+        CHECK(tg_commit(pool, plan, ptrs) == TG_OK && ptrs[0] == base);
+        tg_plan_free(plan);
+    }
 
     /* the Region List and the Tensor Mapping can be read out */
     {

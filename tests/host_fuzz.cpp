@@ -47,6 +47,7 @@ int main(int argc, char **argv) {
                 if (rng() % 10 < 7) flags |= PLAN_MERGE;
                 if (rng() % 2) flags |= PLAN_ALIAS;
                 if (rng() % 2) flags |= PLAN_PACK_TEXT;
+                if (rng() % 3 == 0) flags |= PLAN_CAP_TEXT;
                 std::vector<uint64_t> hits(n, 0);
                 std::vector<std::pair<uint64_t, uint64_t>> cand;
                 for (size_t k = 0; k < n; ++k) {

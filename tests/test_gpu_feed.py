@@ -242,6 +242,37 @@ def test_mistakes_in_a_load_in_steps_end_it_and_leave_the_pool_as_it_was():
     b.close()
 
 
+def test_destroying_a_pool_or_freeing_a_plan_ends_a_load_in_flight():
+    say("pool destroyed / plan freed while a load is in flight")
+    rnd = random.Random(88)
+    tensors = [rbytes(rnd, n) for n in (64 << 20, 4096, 1 << 20)]
+    host, offs = pack(tensors)
+    seg = HostArena(host.size)
+    seg.numpy()[:] = host
+    rows = [(t.size, oracle.fingerprint(t), o) for t, o in zip(tensors, offs)]
+    for how in ("destroy", "free"):
+        p = ReusePool(256 << 20, 256, DEV)
+        plan = tg.tg_plan(p.pool, tg.ModelDesc(1, 0, 0, rows))
+        tg.tg_assemble_begin(p.pool, plan, tg.TG_ASSEMBLE_VERIFY, **stream_args(p))
+        tg.tg_assemble_feed(p.pool, plan, seg.ptr, seg.nbytes, [(0, offs[0]), (1, offs[1])])
+        if how == "destroy":
+            p.close()                              # waits for the streams, gives the load up, frees the tables
+            tg.tg_plan_free(plan)
+        else:
+            tg.tg_plan_free(plan)
+            st = p.stats()
+            assert st["n_entries"] == 0 and st["free_bytes"] == st["capacity"]
+            # the pool goes on working
+            plan = tg.tg_plan(p.pool, tg.ModelDesc(1, seg.ptr, seg.nbytes, rows))
+            ptrs = tg.tg_assemble(p.pool, plan, 3, tg.TG_ASSEMBLE_VERIFY, p.stream_gather, p.stream_h2d)
+            tg.tg_plan_free(plan)
+            for ptr, t in zip(ptrs, tensors):
+                assert p.view(ptr, t.size).cpu().numpy().tobytes() == t.tobytes()
+            p.close()
+    torch.cuda.synchronize()
+    seg.free()
+
+
 def test_async_assemble_returns_before_the_transfer_and_gives_the_same_result():
     say("tg_assemble_async + tg_assemble_wait")
     import time
