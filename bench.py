@@ -77,7 +77,7 @@ def profiled_alu_rate():
 def kernel_shapes(tuning, verify):
     """Template arguments x workgroups per compute unit of the two kernels a load launches."""
     u = lambda v: 16 if v >= 16 else 8 if v >= 8 else 4 if v >= 4 else 2      # noqa: E731
-    fused = "true" if (verify and tuning["fuse_verify"]) else "false"
+    fused = "true" if (verify and tuning["fuse_verify"] & 1) else "false"
     return {"fingerprint": "fingerprint_kernel<256,%d>x%d" % (u(tuning["fingerprint_unroll"]), tuning["fingerprint_wgs_per_cu"]),
             "gather": "gather_kernel<1024,%d,%s>x%d" % (u(tuning["gather_unroll"]), fused, tuning["gather_wgs_per_cu"])}
 

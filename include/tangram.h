@@ -243,11 +243,16 @@ tg_status tg_pool_entries(const tg_pool *pool, tg_entry *out, uint32_t cap, uint
  * threshold of Section 4: missing tensors that are adjacent both in the host
  * image and in the pool are merged into one copy until the copy exceeds this
  * many bytes (the paper's loader uses 8 MB); 0, the default, puts no limit on
- * a merged copy.  fuse_verify (default 1) makes a verifying load compute the
- * fingerprints of the tensors it copies device to device inside the gather
- * launch, from the bytes as they pass through the registers, instead of
- * reading the written slots again with a second launch (0): one pass over HBM
- * less, and it vouches for what was read rather than for what was written.
+ * a merged copy.  fuse_verify is a pair of bits.  Bit 0 (set by default) makes
+ * a verifying load compute the fingerprints of the tensors it copies device to
+ * device inside the gather launch, from the bytes as they pass through the
+ * registers, instead of reading the written slots again with a second launch:
+ * one pass over HBM less, and it vouches for what was read rather than for
+ * what was written.  Bit 1 (clear by default) does the same for the tensors a
+ * merge moves (one that is cut into pieces, or staged, is summed piece by piece
+ * by the launches that write it to its new place); by default they are
+ * fingerprinted where they landed by a launch of their own, which runs beside
+ * the host-to-device copies, whereas the move launches hold those copies up.
  * The defaults (tg_default_tuning) are the measured optimum on
  * MI355X; results never depend on these values.  A pool starts with the
  * defaults.
@@ -258,7 +263,7 @@ typedef struct {
     uint32_t compare_unroll, compare_wgs_per_cu;
     uint64_t h2d_kernel_max_bytes;
     uint64_t h2d_group_bytes;
-    uint32_t fuse_verify;     /* 1: a verifying load fingerprints copied tensors inside the copy launch */
+    uint32_t fuse_verify;     /* bit 0: a verifying load fingerprints copied tensors inside the copy launch; bit 1: moved tensors too */
     uint32_t reserved;        /* must be 0 */
 } tg_tuning;
 tg_status tg_default_tuning(tg_tuning *out);

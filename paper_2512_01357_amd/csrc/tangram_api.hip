@@ -350,8 +350,20 @@ tg_status static_scratch_for(int device, unsigned char **ptr, int *cus) {
 // reads: a stretch whose first byte shifts by d can be copied straight, up to d
 // bytes per launch.  When d is small the stretch is staged instead: one launch
 // gathers up to kBounceBytes into the staging buffer, the next writes them out.
+//
+// Every row remembers which move it is a piece of (slot) and where the piece
+// starts inside the tensor (word0, in 8-byte words; pieces are cut at multiples
+// of 16 bytes), so that a launch can fingerprint the pieces into the tensor's
+// result word.  lands[l] says whether launch l writes into the pool (every
+// byte of every move passes through exactly one such launch).
 tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base, u64 bounce,
-                              std::vector<std::vector<tgk::Copy>> &launches, u64 &traffic) {
+                              std::vector<std::vector<tgk::Copy>> &launches, std::vector<char> &lands, u64 &traffic) {
+    auto piece = [](u64 dst, u64 src, u64 len, size_t move, u64 done) {
+        tgk::Copy c = copy_row(dst, src, len);
+        c.slot = u32(move);
+        c.word0 = done / 8;
+        return c;
+    };
     traffic = 0;
     size_t i = 0;
     uint64_t done = 0;                      // bytes of moves[i] already scheduled
@@ -369,7 +381,7 @@ tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
                 uint64_t len = std::min<uint64_t>(left, src0 - d);
                 if (len < left) len &= ~uint64_t(15);
                 if (len == 0) break;
-                in.push_back(copy_row(base + d, base + s, len));
+                in.push_back(piece(base + d, base + s, len, i, done));
                 traffic += 2 * len;
                 done += len;
                 if (done < m.nbytes) break;                 // cut short: the launch is full
@@ -385,8 +397,8 @@ tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
                 uint64_t len = std::min<uint64_t>(left, kBounceBytes - staged);
                 if (len < left) len &= ~uint64_t(15);
                 if (len == 0) break;
-                in.push_back(copy_row(bounce + staged, base + s, len));
-                out.push_back(copy_row(base + d, bounce + staged, len));
+                in.push_back(piece(bounce + staged, base + s, len, i, done));
+                out.push_back(piece(base + d, bounce + staged, len, i, done));
                 staged += (len + 15) & ~uint64_t(15);
                 traffic += 4 * len;
                 done += len;
@@ -397,7 +409,11 @@ tg_status build_move_launches(const std::vector<tg::Move> &moves, uint64_t base,
         }
         if (in.empty()) return TG_ERR_INVALID;
         launches.push_back(std::move(in));
-        if (!out.empty()) launches.push_back(std::move(out));
+        lands.push_back(out.empty() ? 1 : 0);
+        if (!out.empty()) {
+            launches.push_back(std::move(out));
+            lands.push_back(1);
+        }
     }
     return TG_OK;
 }
@@ -867,11 +883,12 @@ tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_arg
 
     // ---- merge moves (Section 3.2, Stage 2), cut into launches whose reads and writes do not meet
     std::vector<std::vector<tgk::Copy>> move_rows;
+    std::vector<char> move_lands;
     u64 move_traffic = 0;
     if (!pl.moves.empty()) {
         if ((rc = pool->dev.ensure_bounce()) != TG_OK) return rc;
         const u64 bounce = u64(reinterpret_cast<uintptr_t>(pool->dev.bounce));
-        if ((rc = build_move_launches(pl.moves, base, bounce, move_rows, move_traffic)) != TG_OK) return rc;
+        if ((rc = build_move_launches(pl.moves, base, bounce, move_rows, move_lands, move_traffic)) != TG_OK) return rc;
         if ((rc = check_move_launches(move_rows, base, store.capacity(), bounce)) != TG_OK) return rc;
     }
 
@@ -902,7 +919,11 @@ tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_arg
     std::vector<u32> copy_ops;                            // tensor of each row of `copies`
     std::vector<u32> group0;                              // in place without a copy: hits of an aliasing plan
     std::vector<FeedItem> missing;
-    const bool fuse = verify && pool->tune.fuse_verify != 0;
+    const bool fuse = verify && (pool->tune.fuse_verify & 1u) != 0;
+    // Moved tensors: fingerprinting them inside the launches that land them saves a pass over HBM
+    // but lengthens those launches, which every transfer of the load waits for, while a launch of
+    // its own runs beside the transfers; so it is a choice of its own and off by default.
+    const bool fuse_moves = verify && (pool->tune.fuse_verify & 2u) != 0;
     try {
         s.fed.assign(n, 1);
         for (size_t k = 0; k < n; ++k) {
@@ -953,6 +974,21 @@ tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_arg
     CopyLaunch gather;
     FpLaunch fp_moved, fp_group0;
     try {
+        if (fuse_moves && !pl.moves.empty()) {
+            // the launches that land the moved bytes also fingerprint them: one result word per move
+            if (s.results_used + pl.moves.size() > s.results_cap) return TG_ERR_NOMEM;
+            const u32 first = s.results_used;
+            for (size_t i = 0; i < pl.moves.size(); ++i) {
+                s.result_ref.push_back(-1 - int64_t(i));
+                s.t.fused_verify_bytes += pl.moves[i].nbytes;
+            }
+            s.results_used += u32(pl.moves.size());
+            for (size_t l = 0; l < move_rows.size(); ++l) {
+                if (!move_lands[l]) continue;
+                for (tgk::Copy &c : move_rows[l]) c.slot += first;
+                move_launch[l].fused = true;
+            }
+        }
         for (size_t i = 0; i < move_rows.size(); ++i)
             if ((rc = place_copy_launch(s, move_rows[i], move_launch[i])) != TG_OK) return rc;
         if (fuse && !copies.empty()) {
@@ -962,7 +998,7 @@ tg_status session_begin(tg_pool *pool, tg_load_plan *plan, const tg_assemble_arg
         if (!copies.empty() && (rc = place_copy_launch(s, copies, gather)) != TG_OK) return rc;
         if (verify) {
             if ((rc = place_verify(s, group0, false, fp_group0)) != TG_OK) return rc;
-            if (!pl.moves.empty() && (rc = place_verify(s, group0, true, fp_moved)) != TG_OK) return rc;
+            if (!fuse_moves && !pl.moves.empty() && (rc = place_verify(s, group0, true, fp_moved)) != TG_OK) return rc;
         }
     } catch (...) {
         return TG_ERR_NOMEM;
@@ -1031,7 +1067,7 @@ tg_status session_feed(Session &s, const void *seg_base, const std::vector<FeedI
     if (!small_rows.empty()) {
         CopyLaunch cl;
         FpLaunch fp;
-        const bool fuse = s.verify && s.pool->tune.fuse_verify != 0;
+        const bool fuse = s.verify && (s.pool->tune.fuse_verify & 1u) != 0;
         if (fuse) {
             if ((rc = fuse_fingerprints(s, small_rows, small_ops)) != TG_OK) return rc;
             cl.fused = true;

@@ -165,13 +165,16 @@ def test_failed_verification_after_moves_and_evictions_leaves_a_consistent_pool(
     b.close()
 
 
-def test_large_moves_straight_and_staged():
-    say("merge with large shifts (straight copies) and small shifts over long tensors (staged)")
+@pytest.mark.parametrize("fuse", [3, 1])
+def test_large_moves_straight_and_staged(fuse):
+    say("merge with large shifts (straight copies) and small shifts over long tensors (staged); "
+        "moved tensors fingerprinted %s" % ("by the launches that land them" if fuse & 2 else "by a launch of their own"))
     rnd = random.Random(2)
     # F64 A200 F64 B40 F100 (MiB): a 210 MiB tensor fits nowhere; everything is compacted.
     # A shifts by 64 MiB (straight, in pieces of at most 64 MiB), B by 128 MiB.
     b = Both(468 * MIB)
     b.pool.set_profiling(True)
+    b.pool.set_tuning(fuse_verify=fuse)
     carve(b, rnd, [(64, False), (200, True), (64, False), (40, True), (100, False)], MIB)
     plan, _ = b.load(9, [rbytes(rnd, 210 * MIB + 40)], merge=True)
     assert [(o // MIB, n // MIB) for _e, o, n in plan.moves] == [(64, 0), (328, 200)]
@@ -180,21 +183,29 @@ def test_large_moves_straight_and_staged():
     # A goes in pieces of 64 + 64 + 64 + 8 MiB (a launch may not write at or above the first byte
     # it reads, 64 MiB ahead); B's 40 MiB land below that mark too and ride in the last launch
     assert t["move_launches"] == 4
+    # the moved tensors are fingerprinted as well as the new one: piece by piece into one word
+    # each where they land, or in a launch of their own afterwards
+    assert t["fused_verify_bytes"] == (240 * MIB if fuse & 2 else 0)
+    assert t["verify_bytes"] == 210 * MIB + 40 + (0 if fuse & 2 else 240 * MIB)
     b.close()
     # F1 A300 F100 (MiB) + a 101 MiB tensor: A shifts by 1 MiB, staged through 128 MiB at a time
     b = Both(401 * MIB)
+    b.pool.set_tuning(fuse_verify=fuse)
     carve(b, rnd, [(1, False), (300, True), (100, False)], MIB)
     plan, _ = b.load(9, [rbytes(rnd, 101 * MIB - 3)], merge=True)
     assert [(o // MIB, n // MIB) for _e, o, n in plan.moves] == [(1, 0)]
     t = b.pool.last_timing
     assert t["move_launches"] == 6 and t["move_traffic_bytes"] == 4 * 300 * MIB
+    assert t["fused_verify_bytes"] == (300 * MIB if fuse & 2 else 0)
     b.close()
 
 
-def test_a_moved_tensor_that_no_longer_matches_its_row_is_dropped():
-    say("a resident tensor is damaged, then moved by a merging load that verifies")
+@pytest.mark.parametrize("fuse", [3, 2, 1, 0])
+def test_a_moved_tensor_that_no_longer_matches_its_row_is_dropped(fuse):
+    say("a resident tensor is damaged, then moved by a merging load that verifies (fuse_verify=%d)" % fuse)
     rnd = random.Random(78)
     b = Both(30 * U)
+    b.pool.set_tuning(fuse_verify=fuse)
     carve(b, rnd, [(4, False), (2, True), (4, False), (6, True), (4, False), (1, True), (4, False),
                    (1, True), (4, False)], U)
     b.pool.slab[20 * U + 5] ^= 0x10                      # model 105's tensor (moves 20 -> 16 units)
@@ -285,9 +296,11 @@ def test_alias_mode_real_bytes():
 
 @pytest.mark.parametrize("seed", range(4))
 def test_random_histories_with_every_flag_real_bytes(seed):
-    say("random history %d" % seed)
+    fuse = (1, 3, 0, 2)[seed]
+    say("random history %d (fuse_verify=%d)" % (seed, fuse))
     rnd = random.Random(700 + seed)
     b = Both(24 * MIB)
+    b.pool.set_tuning(fuse_verify=fuse)
     library = [rbytes(rnd, rnd.choice([40, 4096, 70000, 300000, 1 << 20, (1 << 20) + 24, 3 << 20, 5000000]))
                for _ in range(20)]
     running, retained, next_id = {}, [], 1
