@@ -294,9 +294,9 @@ def test_alias_mode_real_bytes():
     b.close()
 
 
-@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("seed", range(12))
 def test_random_histories_with_every_flag_real_bytes(seed):
-    fuse = (1, 3, 0, 2)[seed]
+    fuse = (1, 3, 0, 2)[seed % 4]
     say("random history %d (fuse_verify=%d)" % (seed, fuse))
     rnd = random.Random(700 + seed)
     b = Both(24 * MIB)
