@@ -392,6 +392,44 @@ def test_copy_grouping_threshold_changes_the_copies_not_the_result():
     assert copies == {0: 1, 2 * mib: 3, 8 * mib: 1, 1: 8}
 
 
+def _some_size(rnd, tile):
+    r = rnd.random()
+    if r < 0.25:
+        return rnd.randrange(1, 300)
+    if r < 0.45:
+        return rnd.choice([tile, 2 * tile, 3 * tile]) + rnd.randrange(-40, 41)
+    if r < 0.65:
+        return rnd.randrange(1, 1 << 16)
+    if r < 0.9:
+        return rnd.randrange(1 << 16, 4 << 20)
+    return rnd.randrange(4 << 20, 24 << 20)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_models_under_random_launch_shapes(seed):
+    rnd = random.Random(90000 + seed)
+    unroll = rnd.choice([2, 4, 8, 16])
+    tune = dict(gather_unroll=unroll, fingerprint_unroll=rnd.choice([2, 4, 8, 16]), gather_wgs_per_cu=rnd.choice([1, 2]),
+                fingerprint_wgs_per_cu=rnd.choice([1, 2, 4, 8]), fuse_verify=rnd.randrange(4),
+                h2d_kernel_max_bytes=rnd.choice([0, 4096, 65536, 1 << 20]),
+                h2d_group_bytes=rnd.choice([0, 1, 1 << 20, 8 << 20]))
+    align = rnd.choice([16, 256, 4096])
+    say("random model %d: align %d, %s" % (seed, align, tune))
+    b = Pair(512 << 20, align)
+    b.pool.set_tuning(**tune)
+    tile = 1024 * 16 * unroll
+    n = rnd.randrange(1, 40)
+    a = [rbytes(rnd, _some_size(rnd, tile)) for _ in range(n)]
+    b.load_whole(1, a)
+    b.release(1)
+    # a second model that shares about half of the tensors, then a third made of a subset
+    m2 = [a[i] if rnd.random() < 0.5 else rbytes(rnd, _some_size(rnd, tile)) for i in range(n)]
+    b.load_whole(2, m2, verify=rnd.random() < 0.8)
+    b.release(2, evict=rnd.random() < 0.5)
+    b.load_whole(3, [m2[i] for i in rnd.sample(range(n), max(1, n // 2))])
+    b.close()
+
+
 @pytest.mark.parametrize("fuse", [1, 0])
 @pytest.mark.parametrize("unroll", [2, 4, 8, 16])
 def test_a_verifying_load_fingerprints_inside_the_copy_launch_or_after_it(fuse, unroll):
