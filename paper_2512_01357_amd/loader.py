@@ -167,6 +167,7 @@ def concurrent_stream_pair(device: torch.device, candidates: int = 6):
     del a, b, c
     _STREAM_PAIR[key] = best
     _SECOND_H2D[key] = _pick_second_transfer_stream(device, best, [x for x in streams if x not in best], h)
+    _SPARE[key] = [x for x in streams if x not in best and x is not _SECOND_H2D[key]]
     del h
     return best
 
@@ -212,6 +213,70 @@ def _pick_second_transfer_stream(device, pair, others, pinned):
     SECOND_H2D_MEASUREMENT[str(device)] = {"one_stream_ms": round(alone * 1e3, 3), "two_streams_ms": tried}
     del dst, a, b
     return best
+
+
+_SPARE = {}
+_REFILL = {}
+REFILL_MEASUREMENT = {}              # what that choice was based on, per device (for logs)
+
+
+def refill_stream(device: torch.device):
+    """A stream on which a device-to-host copy runs beside the host-to-device
+    copies of a load (the host link carries both directions at once, but only
+    between streams that the runtime keeps apart), or None.  A caller whose
+    Model Cache is refilled by the GPU -- the synthetic tensors here -- does
+    that work on this stream while the previous piece is being copied in.
+    Chosen by measurement, once per device: 1 GiB up on the transfer streams,
+    1 GiB down on the candidate, alone and together; first with both transfer
+    streams of a load in use, then, if nothing runs beside those, with the
+    first one only.  Returns (stream, whether the load may keep its second
+    transfer stream)."""
+    key = str(device)
+    if key in _REFILL:
+        return _REFILL[key]
+    _gather, h2d = concurrent_stream_pair(device)
+    second = _SECOND_H2D.get(key)
+    n = 1 << 30
+    up_h = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    down_h = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    up_d = torch.empty(n, dtype=torch.uint8, device=device)
+    down_d = torch.empty(n, dtype=torch.uint8, device=device)
+    piece = n // 8
+
+    def run(up, down, two=True):
+        torch.cuda.synchronize(device)
+        t0 = time.perf_counter()
+        if up:
+            for k in range(8):
+                st = second if (two and second is not None and k & 1) else h2d
+                with torch.cuda.stream(st):
+                    up_d[k * piece:(k + 1) * piece].copy_(up_h[k * piece:(k + 1) * piece], non_blocking=True)
+        if down is not None:
+            with torch.cuda.stream(down):
+                down_h.copy_(down_d, non_blocking=True)
+        torch.cuda.synchronize(device)
+        return time.perf_counter() - t0
+
+    candidates = list(_SPARE.get(key, [])) + [torch.cuda.Stream(device=device) for _ in range(2)]
+    run(True, candidates[0])
+    best, best_t, keep_second = None, None, True
+    REFILL_MEASUREMENT[key] = {}
+    for two in ([True, False] if second is not None else [False]):
+        up_alone = min(run(True, None, two) for _ in range(2))
+        tried = []
+        for st in candidates:
+            down_alone = min(run(False, st) for _ in range(2))
+            both = min(run(True, st, two) for _ in range(2))
+            tried.append({"down_alone_ms": round(down_alone * 1e3, 2), "both_ms": round(both * 1e3, 2)})
+            if both < 0.75 * (up_alone + down_alone) and (best_t is None or both < best_t):
+                best, best_t, keep_second = st, both, two
+        REFILL_MEASUREMENT[key]["two transfer streams" if two else "one transfer stream"] = {
+            "up_alone_ms": round(up_alone * 1e3, 2), "candidates": tried}
+        if best is not None:
+            break
+    del up_h, down_h, up_d, down_d
+    _REFILL[key] = (best, keep_second)
+    return _REFILL[key]
 
 
 def second_transfer_stream(device: torch.device):
@@ -295,7 +360,7 @@ class ReusePool:
 
     def load_streamed(self, model: RegisteredModel, segments, verify: bool = False, evict: bool = False,
                       merge: bool = False, alias: bool = False, pack_text: bool = False,
-                      cap_text: bool = False, details: bool = True) -> Tuple[List[int], dict]:
+                      cap_text: bool = False, details: bool = True, overlap: bool = False) -> Tuple[List[int], dict]:
         """A load whose missing tensors pass through a Model Cache smaller than
         the model: tg_plan (no host image needed), tg_assemble_begin, then one
         tg_assemble_feed per segment, then tg_assemble_wait.
@@ -310,9 +375,17 @@ class ReusePool:
         kernels and copies.
         info["library_s"] is the time spent inside the library's calls and
         waiting for the device; the rest of the wall time is the generator
-        refilling its buffer."""
+        refilling its buffer.
+
+        With ``overlap`` the generator is resumed right after a piece has been
+        fed, while that piece's copies are in flight, and the wait for them
+        comes afterwards: filling the cache and emptying it run side by side,
+        so the slower of the two sets the time (Eq. 3).  The generator must
+        then fill a buffer other than the one it yielded last.
+        info["overlapped_s"] is the wall time from tg_plan to the end of the
+        load, without the first piece (which the cache holds beforehand)."""
         flags = self._plan_flags(False, evict, merge, alias, pack_text, cap_text)
-        t0 = time.perf_counter()
+        t_start = t0 = time.perf_counter()
         plan = tg.tg_plan(self.pool, model.desc, flags, self.stream_gather)
         lib_s = time.perf_counter() - t0
         try:
@@ -322,18 +395,30 @@ class ReusePool:
                 for key in ("ops", "moves", "evictions"):
                     info.pop(key)
             pieces = iter(segments(missing))
+            t_first = time.perf_counter()
             piece = next(pieces, None)                       # the cache's first piece: there before the load starts
             torch.cuda.synchronize(self.device)
+            t_first = time.perf_counter() - t_first
             t0 = time.perf_counter()
-            tg.tg_assemble_begin(self.pool, plan, tg.TG_ASSEMBLE_VERIFY if verify else 0, **self._stream_args())
+            streams = self._stream_args()
+            if overlap and not refill_stream(self.device)[1]:
+                streams.update(stream_h2d_second=None, use_second_h2d_stream=False)
+            tg.tg_assemble_begin(self.pool, plan, tg.TG_ASSEMBLE_VERIFY if verify else 0, **streams)
             lib_s += time.perf_counter() - t0
             n_feeds = 0
             while piece is not None:
                 ptr, nbytes, rows = piece
                 t0 = time.perf_counter()
                 ticket = tg.tg_assemble_feed(self.pool, plan, ptr, nbytes, rows)
-                tg.tg_assemble_feed_wait(self.pool, plan, ticket)
                 n_feeds += 1
+                if overlap:
+                    lib_s += time.perf_counter() - t0
+                    piece = next(pieces, None)               # the next piece is fetched while this one is copied
+                    t0 = time.perf_counter()
+                    tg.tg_assemble_feed_wait(self.pool, plan, ticket)
+                    lib_s += time.perf_counter() - t0
+                    continue
+                tg.tg_assemble_feed_wait(self.pool, plan, ticket)
                 lib_s += time.perf_counter() - t0
                 # the fingerprints of this piece finish before the refill of the next one starts
                 t0 = time.perf_counter()
@@ -345,6 +430,7 @@ class ReusePool:
             lib_s += time.perf_counter() - t0
             info["timing"] = self.last_timing = tg.tg_plan_timing(plan)
             info["library_s"] = lib_s
+            info["overlapped_s"] = time.perf_counter() - t_start - t_first
             info["feeds"] = n_feeds
         finally:
             tg.tg_plan_free(plan)

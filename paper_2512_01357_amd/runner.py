@@ -1,11 +1,12 @@
 """Runs a synthetic Workload (synth.py) through the library on one GPU."""
+import contextlib
 import time
 from typing import Dict, List, Optional
 
 import torch
 
 from . import synth
-from .loader import HostArena, RegisteredModel, ReusePool
+from .loader import HostArena, RegisteredModel, ReusePool, refill_stream
 
 
 class WorkloadRunner:
@@ -73,10 +74,13 @@ class WorkloadRunner:
             self.log("model cache segment: %.1f GB pinned in %.1f s" % (want / 1e9, time.time() - t0))
         return self.seg_arena
 
-    def segments(self, name: str):
+    def segments(self, name: str, parts: int = 1):
         """A generator factory for ReusePool.load_streamed: given tensor indices
         of model `name`, fills the pinned segment with as many of them as fit,
-        in the given order, and yields (address, length, [(index, offset)])."""
+        in the given order, and yields (address, length, [(index, offset)]).
+        With `parts` > 1 the segment is cut into that many equal buffers that
+        are filled in turn, so that one can be filled while the copies out of
+        another are still in flight."""
         spec = self.w.models[name]
         a = self.w.align
 
@@ -84,21 +88,28 @@ class WorkloadRunner:
             if not ks:
                 return
             slot = [(spec.tensors[k].nbytes + a - 1) // a * a for k in ks]
-            arena = self._segment_arena(max(sum(slot), a))
-            if max(slot) > arena.nbytes:
+            arena = self._segment_arena(max(sum(slot), a) if parts == 1 else self.segment_bytes)
+            part = arena.nbytes if parts == 1 else arena.nbytes // parts // 4096 * 4096
+            if max(slot) > part:
                 raise RuntimeError("a tensor is larger than the Model Cache segment")
-            i = 0
+            # filling one part while another is being copied to the GPU: the tensors are made and
+            # copied to the host on a stream that runs beside the load's transfer streams
+            side = refill_stream(self.pool.device)[0] if parts > 1 else None
+            i = n_yielded = 0
             while i < len(ks):
+                base = (n_yielded % parts) * part
                 rows, at = [], 0
-                while i < len(ks) and at + slot[i] <= arena.nbytes:
-                    t = spec.tensors[ks[i]]
-                    arena.tensor[at:at + t.nbytes].copy_(synth.tensor_bytes(t, self.gen_device))
-                    rows.append((ks[i], at))
-                    at += slot[i]
-                    i += 1
+                with torch.cuda.stream(side) if side is not None else contextlib.nullcontext():
+                    while i < len(ks) and at + slot[i] <= part:
+                        t = spec.tensors[ks[i]]
+                        arena.tensor[base + at:base + at + t.nbytes].copy_(synth.tensor_bytes(t, self.gen_device))
+                        rows.append((ks[i], at))
+                        at += slot[i]
+                        i += 1
                 if self.on_segment is not None:
-                    self.on_segment(name, rows, arena)
-                yield arena.ptr, at, rows
+                    self.on_segment(name, [(k, base + off) for k, off in rows], arena)
+                yield arena.ptr + base, at, rows
+                n_yielded += 1
         return gen
 
     def _register_streamed(self, name: str) -> RegisteredModel:
@@ -186,15 +197,19 @@ class WorkloadRunner:
         for name, (p, b, a) in self.w.costs.items():
             self.pool.set_model_cost(self.w.models[name].model_id, p, b, a)
 
-    def load(self, name: str, confirm: bool = False, verify: bool = False, details: bool = True, **flags):
-        """Loads a model; plan flags default to the workload's for its measured loads."""
+    def load(self, name: str, confirm: bool = False, verify: bool = False, details: bool = True,
+             overlap: bool = False, **flags):
+        """Loads a model; plan flags default to the workload's for its measured loads.
+        `overlap` (models that pass through the Model Cache in pieces): the cache is cut into
+        two halves and one is refilled while the other is being copied to the GPU."""
         reg = self.materialise(name)
         if not flags and name in self.w.loads:
             flags = dict(self.w.load_flags)
         if reg.host is None:
             if confirm:
                 raise ValueError("confirmation needs the model's whole host image")
-            return self.pool.load_streamed(reg, self.segments(name), verify=verify, details=details, **flags)
+            return self.pool.load_streamed(reg, self.segments(name, 2 if overlap else 1), verify=verify,
+                                           details=details, overlap=overlap, **flags)
         return self.pool.load(reg, confirm=confirm, verify=verify, details=details, **flags)
 
     def reset_pool(self) -> None:

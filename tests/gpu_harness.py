@@ -41,7 +41,7 @@ def oracle_fps(host_np, offs, sizes, threads=16):
     return [table[(o, n)] for o, n in zip(offs, sizes)]
 
 
-def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
+def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None, overlap=False):
     """Replays `w` on the library and on the oracle.
 
     Fingerprints, plan rows, returned addresses and pool statistics are
@@ -53,6 +53,8 @@ def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
     every slot is compared with it, beyond that the oracle assembles every
     `sample_every`-th tensor (and the smallest and largest) on its own, from
     the host bytes, and those are compared byte for byte.
+    `overlap`: models that pass through the Model Cache in pieces are loaded with
+    the cache cut in two halves, one refilled while the other is copied.
     """
     r = WorkloadRunner(w, DEV, gen_device=DEV, log=say)
     store = ReuseStoreOracle(w.pool_bytes, w.align)
@@ -114,7 +116,7 @@ def run_workload_both(w, image_limit=1 << 30, sample_every=37, after_load=None):
         rows = list(zip(reg.sizes, want, reg.offs))
         flags = dict(w.load_flags) if name in w.loads else {}
         oplan = store.plan(spec.model_id, rows, host_np if small else None, **flags)
-        ptrs, info = r.load(name, verify=True, **flags)
+        ptrs, info = r.load(name, verify=True, overlap=overlap, **flags)
         assert info["moves"] == [(old, new, e.nbytes) for e, old, new in oplan.moves], name
         assert info["evictions"] == [e.off for e in oplan.evictions], name
         assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops], name

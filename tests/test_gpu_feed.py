@@ -160,6 +160,60 @@ def test_load_in_steps_through_a_small_segment_matches_the_oracle(seg_mib, verif
     b.close()
 
 
+def test_one_half_of_the_segment_is_refilled_while_the_other_is_copied():
+    say("begin / feed / wait: two halves, the next piece written while the previous one is in flight")
+    rnd = random.Random(4242)
+    b = Pair(768 << 20)
+    sizes = [33 << 20, 9 << 20, (1 << 20) + 24, 65537, 4096, 70 << 20, 5000, 24, 40 << 20, 3 * (1 << 20) + 1,
+             64 << 20, 1, 31 << 20, 65536, 17 << 20]
+    a = [rbytes(rnd, n) for n in sizes]
+    b.load_whole(1, a)
+    b.release(1)
+    m2 = [a[i] if i % 4 == 0 else rbytes(rnd, sizes[i]) for i in range(len(sizes))]
+    host, offs = pack(m2)
+    rows = b.rows(m2, offs)
+    oplan = b.store.plan(2, rows, host)
+    plan = tg.tg_plan(b.pool.pool, tg.ModelDesc(2, 0, 0, rows))
+    missing = [k for k, op in enumerate(oplan.ops) if op.kind == 1]
+    half = 72 << 20
+    seg = HostArena(2 * half)
+
+    def fill(part, i):
+        """Writes as many of missing[i:] as fit into half `part`; returns (rows, next i)."""
+        seg_rows, at = [], 0
+        while i < len(missing) and at + sizes[missing[i]] <= half:
+            k = missing[i]
+            seg.numpy()[part * half + at:part * half + at + sizes[k]] = m2[k]
+            seg_rows.append((k, at))
+            at = (at + sizes[k] + 255) // 256 * 256
+            i += 1
+        assert seg_rows, "half too small for a tensor"
+        return seg_rows, i
+
+    piece, i = fill(0, 0)                              # the cache holds the first piece beforehand
+    tg.tg_assemble_begin(b.pool.pool, plan, tg.TG_ASSEMBLE_VERIFY, **stream_args(b.pool))
+    feeds = 0
+    while piece:
+        part = feeds % 2
+        ticket = tg.tg_assemble_feed(b.pool.pool, plan, seg.ptr + part * half, half, piece)
+        feeds += 1
+        # the other half was waited for one turn ago: it may be overwritten while this one is read
+        nxt = None
+        if i < len(missing):
+            seg.numpy()[(1 - part) * half:(2 - part) * half] = 0xEE
+            nxt, i = fill(1 - part, i)
+        tg.tg_assemble_feed_wait(b.pool.pool, plan, ticket)
+        piece = nxt
+    ptrs = tg.tg_assemble_wait(b.pool.pool, plan, len(rows))
+    t = tg.tg_plan_timing(plan)
+    tg.tg_plan_free(plan)
+    assert ptrs == [b.pool.base + d for d in b.store.assemble(oplan, host)]
+    b.check_image()
+    assert t["feeds"] == feeds and feeds >= 4
+    seg.free()
+    b.close()
+
+
 def test_mistakes_in_a_load_in_steps_end_it_and_leave_the_pool_as_it_was():
     say("begin / feed / wait: error paths")
     rnd = random.Random(77)

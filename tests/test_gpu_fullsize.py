@@ -48,15 +48,17 @@ def test_neox_20b_into_a_pool_that_is_too_small_full_size():
     assert p.reused_bytes + p.transfer_bytes == w.models["M20"].nbytes
 
 
-@pytest.mark.parametrize("reuse", [0.0, 0.5, 0.9])
-def test_llama3_70b_full_size(reuse):
+@pytest.mark.parametrize("reuse,overlap", [(0.0, False), (0.5, True), (0.9, False)])
+def test_llama3_70b_full_size(reuse, overlap):
     """Config 5 as one model: one plan of 723 tensors (made without a host image), the missing
-    tensors fed through a pinned segment smaller than the model."""
-    say("full size: Llama-3 70B as one 723-tensor model, reuse %.0f %%" % (reuse * 100))
+    tensors fed through a pinned segment smaller than the model (at 50 %: through its two
+    halves, one refilled while the other is copied)."""
+    say("full size: Llama-3 70B as one 723-tensor model, reuse %.0f %%%s"
+        % (reuse * 100, ", cache halves refilled during the copies" if overlap else ""))
     torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     w = synth.workload_llama70b(reuse, int(free - (16 << 30)))
-    plans, _ = run_workload_both(w)
+    plans, _ = run_workload_both(w, overlap=overlap)
     p = plans["M70"]
     total = w.models["M70"].nbytes
     assert len(p.ops) == 723 and p.reused_bytes + p.transfer_bytes == total
@@ -65,4 +67,6 @@ def test_llama3_70b_full_size(reuse):
     if reuse == 0.0:
         assert sum(1 for op in p.ops if op.kind == 0) == 0      # nothing resident, nothing reused
         assert info["feeds"] >= 3                               # 141 GB through a 48 GB segment
+    if overlap:
+        assert info["feeds"] >= 3                               # 70.6 GB through halves of 24 GB
     say("feeds: %d, library time %.3f s" % (info["feeds"], info["library_s"]))

@@ -43,7 +43,7 @@ class Both:
         self.store = ReuseStoreOracle(capacity, align)
         self.keep = []
 
-    def load(self, mid, tensors, in_steps=0, **fl):
+    def load(self, mid, tensors, in_steps=0, overlap=False, **fl):
         """Loads on both sides.  in_steps > 0: the library plans without a host image and is fed
         the missing tensors in that many pieces (tg_assemble_begin / _feed / _wait)."""
         host, offs = pack(tensors, max(self.align, 16))
@@ -70,7 +70,7 @@ class Both:
                 n = max(1, -(-len(missing) // in_steps))
                 for i in range(0, len(missing), n):
                     yield arena.ptr, arena.nbytes, [(k, offs[k]) for k in missing[i:i + n]]
-            ptrs, info = self.pool.load_streamed(bare, pieces, verify=True, **fl)
+            ptrs, info = self.pool.load_streamed(bare, pieces, verify=True, overlap=overlap, **fl)
         else:
             ptrs, info = self.pool.load(reg, verify=True, **fl)
         assert info["ops"] == [(op.kind, op.dst_off, op.src_off, op.nbytes) for op in oplan.ops]
@@ -313,7 +313,7 @@ def test_random_histories_with_every_flag_real_bytes(seed):
             mid = next_id
             if retained and rnd.random() < 0.25:
                 mid = rnd.choice(retained)
-            plan, dsts = b.load(mid, tensors, in_steps=rnd.choice([0, 0, 1, 3]), **fl)
+            plan, dsts = b.load(mid, tensors, in_steps=rnd.choice([0, 0, 1, 3]), overlap=step % 2 == 1, **fl)
             if plan is None:
                 continue
             running[mid] = (tensors, dsts)
