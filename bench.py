@@ -33,7 +33,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E bandwidth
 METRIC = "effective load GB/s (model bytes resident / load time); fingerprint HBM GB/s"
 PROFILES = os.path.join(ROOT, "profiles")
-TRAFFIC_FILES = ["bench_llama7b_pmc_traffic.txt", "bench_llama70b_reuse90_pmc_traffic.txt"]
+TRAFFIC_FILES = ["bench_llama7b_pmc_traffic.txt", "bench_llama70b_reuse90_pmc_traffic.txt",
+                 "bench_llama70b_reuse50_reuse00_pmc_traffic.txt"]
 ALU_FILE = "alu_mix_probe.txt"
 
 
