@@ -1,11 +1,15 @@
 // Random histories against the host-side Reuse Store, built with
-// -fsanitize=address,undefined by tests/test_host_sanitizers.py.  Checks the
-// structural invariants after every step; the sanitizers check the rest.
+// -fsanitize=address,undefined and with -fsanitize=thread by
+// tests/test_host_sanitizers.py.  Checks the structural invariants after every
+// step; the sanitizers check the rest.  With a second argument the histories
+// are dealt over that many threads, each with stores of its own: the stores
+// share nothing, which is what ThreadSanitizer then confirms.
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <random>
 #include <set>
+#include <thread>
 #include <vector>
 
 #include "../paper_2512_01357_amd/csrc/reuse_store.h"
@@ -17,9 +21,8 @@ static void fail(const char *what, int step) {
     std::exit(1);
 }
 
-int main(int argc, char **argv) {
-    const unsigned seeds = argc > 1 ? unsigned(std::atoi(argv[1])) : 20;
-    for (unsigned seed = 0; seed < seeds; ++seed) {
+static void run_history(unsigned seed) {
+    {
         std::mt19937_64 rng(seed);
         const uint64_t cap = 256ull * (64 + rng() % 400);
         ReuseStore store(1ull << 40, cap, 256);
@@ -127,6 +130,19 @@ int main(int argc, char **argv) {
             if (st.n_regions < st.n_free_regions + st.n_entries) fail("region count", step);
             if (st.n_active > st.n_entries) fail("active count", step);
         }
+    }
+}
+
+int main(int argc, char **argv) {
+    const unsigned seeds = argc > 1 ? unsigned(std::atoi(argv[1])) : 20;
+    const unsigned n_threads = argc > 2 ? unsigned(std::atoi(argv[2])) : 1;
+    if (n_threads <= 1) {
+        for (unsigned seed = 0; seed < seeds; ++seed) run_history(seed);
+    } else {
+        std::vector<std::thread> threads;
+        for (unsigned t = 0; t < n_threads; ++t)
+            threads.emplace_back([=] { for (unsigned seed = t; seed < seeds; seed += n_threads) run_history(seed); });
+        for (auto &th : threads) th.join();
     }
     std::printf("ok %u histories\n", seeds);
     return 0;
