@@ -137,6 +137,33 @@ def test_hand_derived_eviction_and_merge_examples():
     same_stats(pool, store)
     tg.tg_pool_destroy(pool)
 
+    # a subspace begins and ends with a free region: a2 F3 b1 F3 c2 and a tensor of 5 move b only
+    pool = tg.tg_pool_create(FAKE_BASE, 11 * U, 256)
+    store = ReuseStoreOracle(11 * U)
+    layout = [(2, True), (3, False), (1, True), (3, False), (2, True)]
+    for i, (units, keep) in enumerate(layout):
+        rows, hb = layout_rows([units * U], [("S", i)])
+        lp, op = plan_both(pool, store, 100 + i, rows, hb)
+        tg.tg_commit(pool, lp, 1)
+        store.assemble(op)
+        tg.tg_plan_free(lp)
+        tg.tg_release(pool, 100 + i, 0)
+        store.release(100 + i)
+    for i, (units, keep) in enumerate(layout):
+        if not keep:
+            tg.tg_release(pool, 100 + i, tg.TG_RELEASE_EVICT)
+            store.release(100 + i, evict=True)
+    rows, hb = layout_rows([5 * U], ["s0"])
+    lp, op = plan_both(pool, store, 9, rows, hb, merge=True)
+    assert tg.tg_plan_moves(lp) == [(5 * U, 2 * U, U)]
+    assert tg.tg_plan_info(lp)["merge_bound"] == U
+    assert [r[1] // U for r in tg.tg_plan_ops(lp)[0]] == [3]
+    tg.tg_commit(pool, lp, 1)
+    store.assemble(op)
+    tg.tg_plan_free(lp)
+    same_stats(pool, store)
+    tg.tg_pool_destroy(pool)
+
 
 def test_abandoned_plan_keeps_its_evictions_and_moves_only():
     # F4 a2 F4 B6 F4 c1 F4 d1 F4 again: the merge happens, the model does not arrive

@@ -469,6 +469,32 @@ def test_hand_derived_merge_plan():
         (18, 6, False), (24, 6, True)]
 
 
+def test_a_subspace_begins_and_ends_with_a_free_region():
+    # Section 3.2, "Partitioning subspaces": a subspace starts and ends with a free region, so an
+    # allocated region at either end of a stretch is outside it: it is not part of the merge cost
+    # and it never moves.  Units: a2 F3 b1 F3 c2, one incoming tensor of 5.
+    rnd = random.Random(8)
+    s = ReuseStoreOracle(11 * U)
+    kept = carve_layout(s, rnd, [(2, True), (3, False), (1, True), (3, False), (2, True)])
+    assert [(r[1] // U, r[2]) for r in s.regions] == [(2, False), (3, True), (1, False), (3, True), (2, False)]
+    assert subspace(s.regions, 0, 5) == (1, 4) and subspace(s.regions, 0, 1) is None
+    assert subspace(s.regions, 2, 5) == (3, 4)
+    new = [rb(rnd, 5 * U)]
+    host, offs = pack(new)
+    with pytest.raises(NoSpace):
+        s.plan(9, rows(new, offs), host)
+    plan = s.plan(9, rows(new, offs), host, merge=True)
+    assert plan.merge_bound == 1 * U                              # b alone: a and c are outside
+    assert [(o // U, n // U) for _e, o, n in plan.moves] == [(5, 2)]
+    assert [op.dst_off // U for op in plan.ops] == [3]
+    s.assemble(plan, host)
+    assert [(r[0] // U, r[1] // U, r[2]) for r in s.regions] == [
+        (0, 2, False), (2, 1, False), (3, 5, False), (8, 1, True), (9, 2, False)]
+    for mid, t in kept.values():
+        e = next(e for e in s.entries if e.owners == [mid])
+        assert s.image[e.off].tobytes() == t.tobytes()
+
+
 def test_running_tensors_are_walls():
     rnd = random.Random(6)
     s = ReuseStoreOracle(20 * U)

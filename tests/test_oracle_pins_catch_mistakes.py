@@ -178,12 +178,61 @@ def cost_times_bandwidth(self, e):
     return total
 
 
+def capacity_always_free_only(regions, sub, as_printed):
+    return 0 if sub is None else rs.free_bytes(regions, sub)
+
+
+def capacity_always_as_printed(regions, sub, as_printed):
+    return 0 if sub is None else rs.free_bytes(regions, sub) + rs.allocated_bytes(regions, sub)
+
+
+def merge_cost_counts_free_bytes(regions, sub):
+    return sum(r[1] for r in regions[sub[0]:sub[1]] if r[2])
+
+
+def subspace_not_trimmed(regions, lo, hi):
+    return (lo, hi) if any(regions[i][2] for i in range(lo, hi)) else None
+
+
+def stretches_without_walls(regions, movable):
+    sub = rs.subspace(regions, 0, len(regions))
+    return [sub] if sub is not None else []
+
+
+def deal_to_the_smallest_room(regions, subs, sizes, order, cap_as_printed):
+    room = [rs.capacity(regions, sub, cap_as_printed) for sub in subs]
+    subsets = [[] for _ in subs]
+    for k in order:
+        fits = [i for i in range(len(room)) if sizes[k] <= room[i]]
+        if not fits:
+            return None
+        b = min(fits, key=lambda i: (room[i], i))
+        subsets[b].append(k)
+        room[b] -= sizes[k]
+    return subsets
+
+
+def try_packing_text_refuses_exact_fits(sizes, tensors, c1, c2):
+    bins, room = ([], []), [c1, c2]
+    for k in tensors:
+        b = 0 if room[0] >= room[1] else 1
+        if sizes[k] >= room[b]:
+            return [], []
+        bins[b].append(k)
+        room[b] -= sizes[k]
+    return bins
+
+
 def pins_of(*names):
+    """Pin functions by name; a tuple is (name, argument...) for a parametrised pin."""
+    import functools
     import test_oracle_next as nxt
     import test_oracle_store as st
     out = []
     for n in names:
-        out.append(getattr(st, n, None) or getattr(nxt, n))
+        name, args = (n, ()) if isinstance(n, str) else (n[0], n[1:])
+        fn = getattr(st, name, None) or getattr(nxt, name)
+        out.append(functools.partial(fn, *args) if args else fn)
     return out
 
 
@@ -201,6 +250,20 @@ STORE_MISTAKES = [
      ["test_eviction_cost_is_eq_2", "test_hand_derived_eviction_order"]),
     ("Eq. 2 multiplies by the bandwidth", rs.ReuseStoreOracle, "eviction_cost", cost_times_bandwidth,
      ["test_eviction_cost_is_eq_2", "test_hand_derived_eviction_order"]),
+    ("capacity never counts allocated bytes", rs, "capacity", capacity_always_free_only,
+     [("test_packing_example_of_the_paper", True), "test_capacity_as_printed_can_hand_a_subspace_more_than_it_holds"]),
+    ("capacity always counts allocated bytes", rs, "capacity", capacity_always_as_printed,
+     [("test_packing_example_of_the_paper", False), "test_capacity_as_printed_can_hand_a_subspace_more_than_it_holds"]),
+    ("merge cost M counts the free bytes", rs, "allocated_bytes", merge_cost_counts_free_bytes,
+     [("test_packing_example_of_the_paper", False)]),
+    ("a subspace keeps its allocated ends", rs, "subspace", subspace_not_trimmed,
+     ["test_a_subspace_begins_and_ends_with_a_free_region"]),
+    ("running tensors are no walls", rs, "stretches", stretches_without_walls,
+     ["test_running_tensors_are_walls", "test_regions_that_cannot_move_cut_the_pool_into_subspaces"]),
+    ("tensors dealt to the subspace with the least room", rs, "deal_over_stretches", deal_to_the_smallest_room,
+     ["test_regions_that_cannot_move_cut_the_pool_into_subspaces"]),
+    ("the text's packing test refuses exact fits", rs, "try_packing_text", try_packing_text_refuses_exact_fits,
+     ["test_try_packing_as_the_text_words_it"]),
 ]
 
 
@@ -226,7 +289,7 @@ def test_a_wrong_store_function_fails_a_hand_derived_pin(case, monkeypatch):
     for pin in pins:
         try:
             pin()
-        except AssertionError:
+        except (AssertionError, pytest.fail.Exception):     # the latter: an expected NoSpace did not come
             caught += 1
         except (rs.NoSpace, KeyError, IndexError, ValueError):
             caught += 1                         # the mistake broke the plan outright
