@@ -223,6 +223,26 @@ def try_packing_text_refuses_exact_fits(sizes, tensors, c1, c2):
     return bins
 
 
+def smallest_gain_first(regions, pairs, sizes, pack=rs.try_packing, cap_as_printed=False):
+    """Algorithm 1 with the partition points tried by ascending gain."""
+    pending, done = list(pairs), []
+    m = sum(rs.allocated_bytes(regions, sub) for sub, _t in pending)
+    while pending:
+        sub, tensors = pending.pop(0)
+        points = sorted((i for i in range(sub[0], sub[1]) if not regions[i][2]),
+                        key=lambda i: (regions[i][1], regions[i][0]))
+        for p in points:
+            p1, p2 = rs.subspace(regions, sub[0], p), rs.subspace(regions, p + 1, sub[1])
+            t1, t2 = pack(sizes, tensors, rs.capacity(regions, p1, cap_as_printed), rs.capacity(regions, p2, cap_as_printed))
+            if t1 or t2:
+                pending += [(p1, t1), (p2, t2)]
+                m -= regions[p][1]
+                break
+        else:
+            done.append((sub, tensors))
+    return sorted(done, key=lambda st: st[0][0]), m
+
+
 def pins_of(*names):
     """Pin functions by name; a tuple is (name, argument...) for a parametrised pin."""
     import functools
@@ -264,6 +284,8 @@ STORE_MISTAKES = [
      ["test_regions_that_cannot_move_cut_the_pool_into_subspaces"]),
     ("the text's packing test refuses exact fits", rs, "try_packing_text", try_packing_text_refuses_exact_fits,
      ["test_try_packing_as_the_text_words_it"]),
+    ("the smallest gain is tried first", rs, "partitioned_gain_packing", smallest_gain_first,
+     [("test_packing_example_of_the_paper", False), ("test_packing_example_of_the_paper", True)]),
 ]
 
 
