@@ -243,6 +243,42 @@ def smallest_gain_first(regions, pairs, sizes, pack=rs.try_packing, cap_as_print
     return sorted(done, key=lambda st: st[0][0]), m
 
 
+def match_ignores_the_length(self, nbytes, fp, incoming, confirm):
+    best = None
+    for e in self.entries:
+        if e.fp == fp and (best is None or e.off < best.off):
+            best = e
+    return best
+
+
+def match_takes_the_highest_offset(self, nbytes, fp, incoming, confirm):
+    best = None
+    for e in self.entries:
+        if e.fp == fp and e.nbytes == nbytes and (best is None or e.off > best.off):
+            best = e
+    return best
+
+
+def match_never_compares_bytes(self, nbytes, fp, incoming, confirm):
+    best = None
+    for e in self.entries:
+        if e.fp == fp and e.nbytes == nbytes and (best is None or e.off < best.off):
+            best = e
+    return best
+
+
+def free_without_merging(regions, off):
+    for r in regions:
+        if r[0] == off and not r[2]:
+            r[2], r[3] = True, None
+            return
+    raise AssertionError("no allocated region at offset %d" % off)
+
+
+def reuse_size_counts_slots(self, tensors):
+    return sum(rs.round_up(n, self.align) for n, fp, _o in tensors if self._match(n, fp, None, False) is not None)
+
+
 def pins_of(*names):
     """Pin functions by name; a tuple is (name, argument...) for a parametrised pin."""
     import functools
@@ -284,6 +320,16 @@ STORE_MISTAKES = [
      ["test_regions_that_cannot_move_cut_the_pool_into_subspaces"]),
     ("the text's packing test refuses exact fits", rs, "try_packing_text", try_packing_text_refuses_exact_fits,
      ["test_try_packing_as_the_text_words_it"]),
+    ("the match key is the fingerprint alone", rs.ReuseStoreOracle, "_match", match_ignores_the_length,
+     ["test_same_bytes_different_length_do_not_match"]),
+    ("of several resident copies the highest offset wins", rs.ReuseStoreOracle, "_match", match_takes_the_highest_offset,
+     ["test_duplicates_inside_one_model_and_across_models"]),
+    ("confirm trusts the fingerprint", rs.ReuseStoreOracle, "_match", match_never_compares_bytes,
+     ["test_confirm_demotes_a_constructed_collision"]),
+    ("freed regions are not merged with free neighbours", rs, "free_at", free_without_merging,
+     ["test_release_keeps_tensors_matchable_until_evicted"]),
+    ("the reuse size counts padded slots", rs.ReuseStoreOracle, "reuse_size", reuse_size_counts_slots,
+     ["test_reuse_size_counts_resident_bytes"]),
     ("the smallest gain is tried first", rs, "partitioned_gain_packing", smallest_gain_first,
      [("test_packing_example_of_the_paper", False), ("test_packing_example_of_the_paper", True)]),
 ]
