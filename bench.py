@@ -472,7 +472,7 @@ def bench_resident(args, torch, w, link_peak, steps, warmup, with_extras, with_c
 
 
 # ------------------------------------------------------------------ config 5: the 70B model, one plan, segmented Model Cache
-def bench_llama70b(args, torch, link_peak, levels, steps, warmup):
+def bench_llama70b(args, torch, link_peak, levels, steps, warmup, legs=None):
     """One pool that holds the 90 % sibling; per reuse level `steps` timed loads of the whole
     723-tensor model.  The pinned Model Cache segment is smaller than what a load transfers, so
     it is refilled between feeds; refilling (here: regenerating the synthetic tensors) is outside
@@ -498,7 +498,7 @@ def bench_llama70b(args, torch, link_peak, levels, steps, warmup):
     verify = not args.no_verify
     if args.pmc_calibration:
         pmc_calibration_kernel(torch)
-    legs = []
+    legs = [] if legs is None else legs          # filled as the legs finish, so that a caller keeps what was measured
     for name in w.loads:
         r.materialise(name)
         recs, walls = [], []
@@ -656,7 +656,12 @@ def main():
     legs = args.legs if args.legs is not None else ("90,50,0" if args.workload == "llama7b" else "none")
     if legs != "none":
         levels = tuple(int(x) / 100.0 for x in re.split(r"[ ,]+", legs.strip()) if x)
-        out["legs"] = bench_llama70b(args, torch, link_peak, levels, args.leg_steps, args.leg_warmup)
+        out["legs"] = []
+        try:
+            bench_llama70b(args, torch, link_peak, levels, args.leg_steps, args.leg_warmup, out["legs"])
+        except Exception as e:          # the headline above stands on its own: report it with the legs that finished
+            log("70B legs stopped: %r" % (e,))
+            out["legs_error"] = repr(e)
     print(json.dumps(out), flush=True)
 
 
